@@ -1,0 +1,82 @@
+// Device-side helpers shared by all kernels: bf16 conversion, the MFMA operand
+// order used for GEMM inputs, in-page placement of K and V, wave reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hydra {
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ bf16_t f2bf(float f) {          // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);   // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+template <bool BF> struct Elem;
+template <> struct Elem<true>  { typedef bf16_t type; static __device__ __forceinline__ float ld(const bf16_t *p, size_t i) { return bf2f(p[i]); }
+                                 static __device__ __forceinline__ void st(bf16_t *p, size_t i, float v) { p[i] = f2bf(v); } };
+template <> struct Elem<false> { typedef float type;  static __device__ __forceinline__ float ld(const float *p, size_t i) { return p[i]; }
+                                 static __device__ __forceinline__ void st(float *p, size_t i, float v) { p[i] = v; } };
+
+// ---- GEMM input order ------------------------------------------------------
+// bf16 family: activations X[M][K] are stored as 32-row x 16-column tiles in
+// the register order of the 32x32x16 MFMA "A" operand: lane = (k%16)/8*32 + m%32
+// holds 8 consecutive k.  Tile (mb, kt) is the 1 KiB block number mb*KT + kt.
+// f32 family: plain row-major.
+template <bool BF>
+__device__ __forceinline__ size_t x_index(int m, int k, int K) {
+    if (BF) {
+        const int KT = K >> 4;
+        return ((((size_t)(m >> 5) * KT + (k >> 4)) * 64 + ((k >> 3) & 1) * 32 + (m & 31)) << 3) + (k & 7);
+    } else {
+        return (size_t)m * K + k;
+    }
+}
+
+// ---- KV cache placement ------------------------------------------------------
+// One (layer, page, head) block holds 16 tokens x Dh dims.
+//   f32 : K and V row-major [token][dim].
+//   bf16: K as [dim/8][token][dim%8]   (16-byte runs = MFMA operand rows for S^T = K Q^T),
+//         V as [dim][perm(token)]      (16-byte runs = MFMA operand rows for O^T = V^T P^T)
+//         with perm(t) = ((t>>2)&1)*8 + (t>>3)*4 + (t&3), the order in which a lane
+//         of the 32x32 accumulator holds the 16 keys of a page.
+template <bool BF> __device__ __forceinline__ int k_in_block(int tok, int dim, int Dh) {
+    return BF ? (((dim >> 3) * 16 + tok) << 3) + (dim & 7) : tok * Dh + dim;
+}
+__device__ __forceinline__ int v_perm(int t) { return ((t >> 2) & 1) * 8 + (t >> 3) * 4 + (t & 3); }
+template <bool BF> __device__ __forceinline__ int v_in_block(int tok, int dim, int Dh) {
+    return BF ? dim * 16 + v_perm(tok) : tok * Dh + dim;
+}
+__device__ __forceinline__ size_t kv_block_base(int layer, int n_pages, int page, int H, int head, int Dh) {
+    return ((((size_t)layer * n_pages + page) * H) + head) * (size_t)(16 * Dh);
+}
+
+// ---- wave reductions (64 lanes) ------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// sum of S split-K partial results of one output element
+__device__ __forceinline__ float part_sum(const float *part, int S, size_t split_stride, size_t idx) {
+    float a = part[idx];
+    for (int s = 1; s < S; ++s) a += part[(size_t)s * split_stride + idx];
+    return a;
+}
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+
+enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2 };
+
+}  // namespace hydra

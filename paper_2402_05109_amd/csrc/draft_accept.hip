@@ -1,0 +1,324 @@
+// Kernels of the draft phases (gather/concat, bias + SiLU, wave-level top-k)
+// and of the integer tail of a step (greedy acceptance, cache compaction,
+// state update).
+#include "device_common.h"
+#include "internal.h"
+
+namespace hydra {
+
+// tree_tokens[b, 0] = root[b]   (node 0 is x_t)
+__global__ void draft_root_kernel(const int32_t *root, int32_t *tree_tokens, int B, int T) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < B) tree_tokens[(size_t)b * T] = root[b];
+}
+
+int launch_draft_root(hydra_ctx *c, hipStream_t s, int B, const int32_t *root, int32_t *tree_tokens) {
+    hipLaunchKernelGGL(draft_root_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, s, root, tree_tokens, B, c->tree.T);
+    HYDRA_LAUNCH_CHECK("draft_root_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Head input (paper, section 3): for expanding node n of phase i (depth i-1),
+//   u = [h_last ; E[tok(p_0)] ; ... ; E[tok(p_{i-1})]],  p_0 = root, p_{i-1} = n,
+// concatenated on the feature axis.  Row r = b * n_expand + j.
+// grid = (rows, segments); segment 0 copies h_last, segment s >= 1 one embedding.
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_root, const float *h_last,
+                                    const int32_t *tree_tokens, const typename Elem<BF>::type *E, int d, int V,
+                                    int Kin, typename Elem<BF>::type *out, int32_t *flags) {
+    const int ne = tree->n_expand[phase];
+    const int r = blockIdx.x, seg = blockIdx.y;
+    const int b = r / ne, j = r - b * ne;
+    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
+    if (seg == 0) {
+        for (int k = threadIdx.x; k < d; k += blockDim.x)
+            Elem<BF>::st(out, x_index<BF>(r, k, Kin), h_last[(size_t)b * d + k]);
+        return;
+    }
+    // embedding of the path node at depth dd; n itself has depth phase-1
+    const int dd = seg - 1 + (include_root ? 0 : 1);
+    int a = n;
+    for (int up = (phase - 1) - dd; up > 0; --up) a = tree->parent[a];
+    int tok = tree_tokens[(size_t)b * tree->T + a];
+    if (tok < 0 || tok >= V) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
+        tok = 0;
+    }
+    for (int k = threadIdx.x; k < d; k += blockDim.x)
+        out[x_index<BF>(r, seg * d + k, Kin)] = E[(size_t)tok * d + k];
+}
+
+int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const float *h_last,
+                        const int32_t *tree_tokens, void *x_out, int32_t *flags) {
+    const int ne = c->tree.n_expand[phase];
+    const int inc = c->h.include_root_embedding ? 1 : 0;
+    const int nseg = 1 + (inc ? phase : phase - 1);
+    const int Kin = nseg * c->m.d;
+    dim3 grid(B * ne, nseg), block(256);
+    const void *E = c->arena + c->off_embed;
+    if (c->bf16) hipLaunchKernelGGL(draft_gather_kernel<true>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const bf16_t *)E, c->m.d, c->m.vocab, Kin, (bf16_t *)x_out, flags);
+    else         hipLaunchKernelGGL(draft_gather_kernel<false>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const float *)E, c->m.d, c->m.vocab, Kin, (float *)x_out, flags);
+    HYDRA_LAUNCH_CHECK("draft_gather_kernel");
+    return HYDRA_OK;
+}
+
+// z <- (residual ? z : 0) + SiLU(W u + b);  also written as the next GEMM input
+template <bool BF>
+__global__ void bias_silu_kernel(const float *part, int S, int part_ld, size_t split_stride, const float *bias,
+                                 float *z, int residual, int d, typename Elem<BF>::type *out) {
+    const int m = blockIdx.y;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= d) return;
+    float a = silu_f(part_sum(part, S, split_stride, (size_t)m * part_ld + k) + bias[k]);
+    if (residual) a += z[(size_t)m * d + k];
+    z[(size_t)m * d + k] = a;
+    Elem<BF>::st(out, x_index<BF>(m, k, d), a);
+}
+
+int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
+                     const float *bias, float *z, bool residual, void *x_out, int M) {
+    dim3 grid(ceil_div(c->m.d, 256), M), block(256);
+    if (c->bf16) hipLaunchKernelGGL(bias_silu_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, bias, z, residual ? 1 : 0, c->m.d, (bf16_t *)x_out);
+    else         hipLaunchKernelGGL(bias_silu_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, bias, z, residual ? 1 : 0, c->m.d, (float *)x_out);
+    HYDRA_LAUNCH_CHECK("bias_silu_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Top-k per row, ordered by (logit descending, token id ascending) (paper,
+// section 2: children are the m most likely tokens, sorted).
+// One workgroup of 16 waves per row.  Each lane keeps up to 32 logits in
+// registers; every wave extracts its own k best with k rounds of a wave-wide
+// reduction (no workgroup barrier), the 16 x k survivors go to LDS and wave 0
+// extracts the final k from them the same way.
+// ---------------------------------------------------------------------------
+struct Cand { float v; int id; };
+__device__ __forceinline__ bool better(float v, int id, float w, int jd) { return v > w || (v == w && id < jd); }
+__device__ __forceinline__ Cand wave_best(Cand c) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float w = __shfl_xor(c.v, o, 64);
+        const int jd = __shfl_xor(c.id, o, 64);
+        if (better(w, jd, c.v, c.id)) { c.v = w; c.id = jd; }
+    }
+    return c;
+}
+
+enum { TOPK_THREADS = 1024, TOPK_PER_LANE = 32 };
+
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, int S, int part_ld, size_t split_stride,
+                                                             int V, const TreeDev *tree, int phase,
+                                                             int32_t *tree_tokens) {
+    const int ne = tree->n_expand[phase];
+    const int r = blockIdx.x;
+    const int b = r / ne, j = r - b * ne;
+    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
+    const int k = tree->n_children[n];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    float val[TOPK_PER_LANE];
+    uint32_t live = 0;
+#pragma unroll
+    for (int i = 0; i < TOPK_PER_LANE; ++i) {
+        const int id = i * TOPK_THREADS + threadIdx.x;
+        val[i] = -INFINITY;
+        if (id < V) {
+            val[i] = part_sum(part, S, split_stride, (size_t)r * part_ld + id);
+            live |= 1u << i;
+        }
+    }
+    __shared__ Cand surv[16 * HYDRA_MAX_TOPK];
+    for (int t = 0; t < k; ++t) {
+        Cand c = {-INFINITY, 0x7fffffff};
+        int slot = -1;
+#pragma unroll
+        for (int i = 0; i < TOPK_PER_LANE; ++i) {
+            const int id = i * TOPK_THREADS + threadIdx.x;
+            if (((live >> i) & 1u) && (slot < 0 || better(val[i], id, c.v, c.id))) { c.v = val[i]; c.id = id; slot = i; }
+        }
+        const Cand w = wave_best(c);
+        if (slot >= 0 && w.id == c.id) live &= ~(1u << slot);      // the winner's owner retires it
+        if (lane == 0) surv[wave * HYDRA_MAX_TOPK + t] = w;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    // 16 * k survivors, k <= 32: lane holds up to 8 of them
+    Cand mine[8];
+    uint32_t mlive = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int q = i * 64 + lane;                  // survivor index: wave = q / k, rank = q % k
+        mine[i].v = -INFINITY; mine[i].id = 0x7fffffff;
+        if (q < 16 * k) {
+            mine[i] = surv[(q / k) * HYDRA_MAX_TOPK + (q % k)];
+            if (mine[i].id != 0x7fffffff) mlive |= 1u << i;
+        }
+    }
+    const int first = tree->first_child[n];
+    for (int t = 0; t < k; ++t) {
+        Cand c = {-INFINITY, 0x7fffffff};
+        int slot = -1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (((mlive >> i) & 1u) && (slot < 0 || better(mine[i].v, mine[i].id, c.v, c.id))) { c = mine[i]; slot = i; }
+        const Cand w = wave_best(c);
+        if (slot >= 0 && w.id == c.id) mlive &= ~(1u << slot);
+        if (lane == 0) tree_tokens[(size_t)b * tree->T + first + t] = w.id;
+    }
+}
+
+// Any-V fallback: k rounds over memory, each picking the best entry that comes
+// strictly after the previous winner in the (value desc, id asc) order.
+__global__ __launch_bounds__(256) void topk_scan_kernel(const float *part, int S, int part_ld, size_t split_stride,
+                                                         int V, const TreeDev *tree, int phase, int32_t *tree_tokens) {
+    const int ne = tree->n_expand[phase];
+    const int r = blockIdx.x;
+    const int b = r / ne, j = r - b * ne;
+    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
+    const int k = tree->n_children[n];
+    __shared__ Cand red[4];
+    __shared__ Cand prev;
+    if (threadIdx.x == 0) { prev.v = INFINITY; prev.id = -1; }
+    __syncthreads();
+    for (int t = 0; t < k; ++t) {
+        const Cand p = prev;
+        Cand c = {-INFINITY, 0x7fffffff};
+        for (int id = threadIdx.x; id < V; id += 256) {
+            const float v = part_sum(part, S, split_stride, (size_t)r * part_ld + id);
+            const bool after = better(p.v, p.id, v, id);
+            if (after && better(v, id, c.v, c.id)) { c.v = v; c.id = id; }
+        }
+        c = wave_best(c);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            Cand w = red[0];
+            for (int i = 1; i < 4; ++i) if (better(red[i].v, red[i].id, w.v, w.id)) w = red[i];
+            prev = w;
+            tree_tokens[(size_t)b * tree->T + tree->first_child[n] + t] = w.id;
+        }
+        __syncthreads();
+    }
+}
+
+int launch_topk(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, int B,
+                int phase, int32_t *tree_tokens) {
+    const int rows = B * c->tree.n_expand[phase];
+    if (c->m.vocab <= TOPK_THREADS * TOPK_PER_LANE)
+        hipLaunchKernelGGL(topk_kernel, dim3(rows), dim3(TOPK_THREADS), 0, s, part, S, part_ld, split_stride, c->m.vocab, tree_dev(c), phase, tree_tokens);
+    else
+        hipLaunchKernelGGL(topk_scan_kernel, dim3(rows), dim3(256), 0, s, part, S, part_ld, split_stride, c->m.vocab, tree_dev(c), phase, tree_tokens);
+    HYDRA_LAUNCH_CHECK("topk_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Greedy acceptance (paper, section 2): walk down from the root while some
+// child carries the base model's most likely token.  One thread per row.
+// ---------------------------------------------------------------------------
+__global__ void accept_kernel(const TreeDev *tree, int B, const int32_t *tree_tokens, const int32_t *argmax,
+                              int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int T = tree->T, plen = tree->max_depth + 1;
+    const int32_t *tok = tree_tokens + (size_t)b * T;
+    const int32_t *am = argmax + (size_t)b * T;
+    int32_t *p = path + (size_t)b * plen;
+    int cur = 0, len = 1;
+    p[0] = 0;
+    for (;;) {
+        const int g = am[cur];
+        const int fc = tree->first_child[cur], nc = tree->n_children[cur];
+        int nxt = -1;
+        for (int i = 0; i < nc; ++i)
+            if (tok[fc + i] == g) { nxt = fc + i; break; }
+        if (nxt < 0) break;
+        cur = nxt;
+        p[len++] = cur;
+    }
+    for (int i = len; i < plen; ++i) p[i] = -1;
+    n_acc[b] = len;
+    next_root[b] = am[cur];
+    last_node[b] = cur;
+}
+
+int launch_accept(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens, const int32_t *argmax,
+                  int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node) {
+    hipLaunchKernelGGL(accept_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, s, tree_dev(c), B, tree_tokens, argmax, n_acc, path, next_root, last_node);
+    HYDRA_LAUNCH_CHECK("accept_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Cache compaction: slot L + path[j] -> slot L + j for j < n_acc, every layer.
+// A thread owns one (layer, head, dim) element column and walks j upwards;
+// path[j] >= j and strictly increasing, so within a column every source is read
+// before it can be overwritten and no two threads touch the same element.
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ void compact_kernel(const TreeDev *tree, const int32_t *n_acc, const int32_t *path,
+                               const int32_t *seq_len, const int32_t *page_table, int max_pages, int n_pages,
+                               typename Elem<BF>::type *kpages, typename Elem<BF>::type *vpages, int H, int Dh) {
+    const int h = blockIdx.x, layer = blockIdx.y, b = blockIdx.z;
+    const int dim = threadIdx.x;
+    if (dim >= Dh) return;
+    const int L = seq_len[b];
+    if (L < 0 || L + tree->T > max_pages * 16) return;     // row was skipped by the verify kernels
+    const int plen = tree->max_depth + 1;
+    int na = n_acc[b];
+    na = na < 0 ? 0 : (na > plen ? plen : na);
+    for (int j = 0; j < na; ++j) {
+        const int n = path[(size_t)b * plen + j];
+        if (n == j || n < 0 || n >= tree->T) continue;
+        const int ss = L + n, ds = L + j;
+        const size_t sb = kv_block_base(layer, n_pages, page_table[(size_t)b * max_pages + (ss >> 4)], H, h, Dh);
+        const size_t db = kv_block_base(layer, n_pages, page_table[(size_t)b * max_pages + (ds >> 4)], H, h, Dh);
+        kpages[db + k_in_block<BF>(ds & 15, dim, Dh)] = kpages[sb + k_in_block<BF>(ss & 15, dim, Dh)];
+        vpages[db + v_in_block<BF>(ds & 15, dim, Dh)] = vpages[sb + v_in_block<BF>(ss & 15, dim, Dh)];
+    }
+}
+
+// h_last <- hidden[last accepted node]; root <- next_root; seq_len += n_acc;
+// kv_index[j] = (physical page, offset) of slot L + j.  Runs after compact_kernel.
+__global__ void state_update_kernel(const TreeDev *tree, const int32_t *n_acc, const int32_t *next_root,
+                                    const int32_t *last_node, const float *hidden, const int32_t *page_table,
+                                    int max_pages, int d, int32_t *seq_len, float *h_last, int32_t *root,
+                                    int32_t *kv_index) {
+    const int b = blockIdx.x;
+    const int T = tree->T, plen = tree->max_depth + 1;
+    const int L = seq_len[b];
+    int na = n_acc[b];
+    na = na < 0 ? 0 : (na > plen ? plen : na);
+    int last = last_node[b];
+    last = last < 0 ? 0 : (last >= T ? T - 1 : last);
+    for (int k = threadIdx.x; k < d; k += blockDim.x) h_last[(size_t)b * d + k] = hidden[((size_t)b * T + last) * d + k];
+    __syncthreads();                                        // every thread has read seq_len[b]
+    if (threadIdx.x == 0) {
+        root[b] = next_root[b];
+        if (kv_index) {
+            const bool ok = L >= 0 && L + T <= max_pages * 16;
+            for (int j = 0; j < plen; ++j) {
+                const bool in = ok && j < na;
+                kv_index[((size_t)b * plen + j) * 2 + 0] = in ? page_table[(size_t)b * max_pages + ((L + j) >> 4)] : -1;
+                kv_index[((size_t)b * plen + j) * 2 + 1] = in ? ((L + j) & 15) : -1;
+            }
+        }
+        seq_len[b] = L + na;
+    }
+}
+
+int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, const int32_t *path,
+                   const int32_t *next_root, const int32_t *last_node, const float *hidden, const hydra_kv *kv,
+                   int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index) {
+    dim3 grid(c->m.n_heads, c->m.n_layers, B), block(c->m.head_dim);
+    if (c->bf16) hipLaunchKernelGGL(compact_kernel<true>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, c->m.n_heads, c->m.head_dim);
+    else         hipLaunchKernelGGL(compact_kernel<false>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (float *)kv->k_pages, (float *)kv->v_pages, c->m.n_heads, c->m.head_dim);
+    HYDRA_LAUNCH_CHECK("compact_kernel");
+    hipLaunchKernelGGL(state_update_kernel, dim3(B), dim3(256), 0, s, tree_dev(c), n_acc, next_root, last_node, hidden, kv->page_table, kv->max_pages, c->m.d, seq_len, h_last, root, kv_index);
+    HYDRA_LAUNCH_CHECK("state_update_kernel");
+    return HYDRA_OK;
+}
+
+}  // namespace hydra

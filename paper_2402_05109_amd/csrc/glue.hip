@@ -1,0 +1,282 @@
+// Elementwise / gather / reduce kernels around the GEMMs and the attention:
+// embedding gather, residual + RMSNorm, rotary + KV append, SiLU*up,
+// LM-head argmax, plain <-> in-page KV conversion.  Each kernel is written once
+// and instantiated for the two storage families (BF = bf16, !BF = fp32).
+#include "device_common.h"
+#include "internal.h"
+
+namespace hydra {
+
+// ---------------------------------------------------------------------------
+// x[m, :] = E[token[m], :]      (tree verification: "packing all of the tree's
+// tokens into a single input sequence", paper section 2)
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ void embed_kernel(const typename Elem<BF>::type *E, const int32_t *tokens, float *x, int d, int V,
+                             int32_t *flags) {
+    const int m = blockIdx.x;
+    int tok = tokens[m];
+    if (tok < 0 || tok >= V) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
+        tok = 0;
+    }
+    for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)m * d + k] = Elem<BF>::ld(E, (size_t)tok * d + k);
+}
+
+int launch_embed(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, int M, int32_t *flags) {
+    const void *E = c->arena + c->off_embed;
+    if (c->bf16) hipLaunchKernelGGL(embed_kernel<true>, dim3(M), dim3(256), 0, s, (const bf16_t *)E, tokens, x, c->m.d, c->m.vocab, flags);
+    else         hipLaunchKernelGGL(embed_kernel<false>, dim3(M), dim3(256), 0, s, (const float *)E, tokens, x, c->m.d, c->m.vocab, flags);
+    HYDRA_LAUNCH_CHECK("embed_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Residual add + RMSNorm.  x[m,:] += sum_s part[s][m,:]  (if S > 0), then
+// out[m,k] = x[m,k] * gain[k] / sqrt(mean_k x^2 + eps), written as the next
+// GEMM's input and, for the final norm, also as fp32 `hidden`.
+// One workgroup per row; a thread keeps its <= 32 elements in registers.
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *part, int S, int part_ld,
+                                                       size_t split_stride, const float *gain, float eps, int d,
+                                                       typename Elem<BF>::type *out, float *hidden) {
+    const int m = blockIdx.x;
+    float v[32];
+    float ss = 0.f;
+    int cnt = 0;
+    for (int k = threadIdx.x; k < d; k += 256, ++cnt) {
+        float a = x[(size_t)m * d + k];
+        if (S > 0) {
+            a += part_sum(part, S, split_stride, (size_t)m * part_ld + k);
+            x[(size_t)m * d + k] = a;
+        }
+        v[cnt] = a;
+        ss += a * a;
+    }
+    __shared__ float red[4];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float rstd = 1.0f / sqrtf(tot / (float)d + eps);
+    cnt = 0;
+    for (int k = threadIdx.x; k < d; k += 256, ++cnt) {
+        const float y = v[cnt] * rstd * gain[k];
+        Elem<BF>::st(out, x_index<BF>(m, k, d), y);
+        if (hidden) hidden[(size_t)m * d + k] = y;
+    }
+}
+
+int launch_rmsnorm(hydra_ctx *c, hipStream_t s, float *x, const float *part, int S, int part_ld,
+                   size_t split_stride, const float *gain, void *x_out, int M, float *hidden_out) {
+    if (c->m.d > 32 * 256) return fail(HYDRA_E_UNSUPPORTED, "rmsnorm: d > 8192");
+    if (c->bf16) hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(256), 0, s, x, part, S, part_ld, split_stride, gain, c->m.rms_eps, c->m.d, (bf16_t *)x_out, hidden_out);
+    else         hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(256), 0, s, x, part, S, part_ld, split_stride, gain, c->m.rms_eps, c->m.d, (float *)x_out, hidden_out);
+    HYDRA_LAUNCH_CHECK("rmsnorm_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Rotary embedding of q and k at position seq_len[b] + depth[n], then
+//   q -> attention input buffer, (k, v) -> cache slot seq_len[b] + n.
+// Input: the QKV GEMM result, columns [0,d) = q, [d,2d) = k, [2d,3d) = v.
+// One workgroup per (row m = b*T + n, head); thread j < Dh/2 owns the rotary
+// pair (j, j + Dh/2).
+//
+// q buffer layout.  f32 family: [B][T][H][Dh] fp32.  bf16 family: per (b, head,
+// 32-query tile qt) a run of Dh/16 blocks of 1 KiB in MFMA operand order:
+// block s, lane = ((dim>>3)&1)*32 + query%32 holds dims (dim>>3)*8 .. +8.
+// ---------------------------------------------------------------------------
+template <bool BF>
+__device__ __forceinline__ size_t q_index(int b, int n, int h, int dim, int H, int Dh, int T) {
+    if (BF) {
+        const int QT = (T + 31) >> 5, KS = Dh >> 4;
+        const size_t blk = (((size_t)b * H + h) * QT + (n >> 5)) * KS + (dim >> 4);
+        return ((blk * 64 + ((dim >> 3) & 1) * 32 + (n & 31)) << 3) + (dim & 7);
+    } else {
+        return (((size_t)b * T + n) * H + h) * Dh + dim;
+    }
+}
+
+template <bool BF>
+__global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t split_stride, const TreeDev *tree,
+                                   const float *rope, const int32_t *seq_len, const int32_t *page_table,
+                                   int max_pages, int n_pages, int layer, typename Elem<BF>::type *kpages,
+                                   typename Elem<BF>::type *vpages, typename Elem<BF>::type *qbuf, int d, int H,
+                                   int Dh, int max_pos, int32_t *flags) {
+    const int T = tree->T;
+    const int m = blockIdx.x, h = blockIdx.y;
+    const int b = m / T, n = m - b * T;
+    const int L = seq_len[b];
+    const int slot = L + n;
+    const int pos = L + tree->depth[n];
+    const bool ok = L >= 0 && (L + T) <= max_pages * 16 && (L + tree->max_depth) < max_pos;
+    if (!ok) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_CAPACITY);
+        return;
+    }
+    const int half = Dh >> 1;
+    const int j = threadIdx.x;
+    if (j >= half) return;
+    const size_t row = (size_t)m * part_ld;
+    const int c0 = h * Dh + j, c1 = c0 + half;
+    const float q0 = part_sum(part, S, split_stride, row + c0), q1 = part_sum(part, S, split_stride, row + c1);
+    const float k0 = part_sum(part, S, split_stride, row + d + c0), k1 = part_sum(part, S, split_stride, row + d + c1);
+    const float v0 = part_sum(part, S, split_stride, row + 2 * d + c0), v1 = part_sum(part, S, split_stride, row + 2 * d + c1);
+    const float cs = rope[((size_t)pos * half + j) * 2], sn = rope[((size_t)pos * half + j) * 2 + 1];
+    Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
+    Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
+    const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
+    const int tok = slot & 15;
+    const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
+    Elem<BF>::st(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn);
+    Elem<BF>::st(kpages, base + k_in_block<BF>(tok, j + half, Dh), k1 * cs + k0 * sn);
+    Elem<BF>::st(vpages, base + v_in_block<BF>(tok, j, Dh), v0);
+    Elem<BF>::st(vpages, base + v_in_block<BF>(tok, j + half, Dh), v1);
+}
+
+int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
+                       int B, int layer, const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags) {
+    const int T = c->tree.T;
+    dim3 grid(B * T, c->m.n_heads), block(64);
+    if (c->bf16)
+        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, (bf16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+    else
+        hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+    HYDRA_LAUNCH_CHECK("rope_append_kernel");
+    return HYDRA_OK;
+}
+
+// fp32 [B,T,H,Dh] q (already rotated) -> attention input buffer (tree_attention entry point)
+template <bool BF>
+__global__ void q_import_kernel(const float *q, typename Elem<BF>::type *qbuf, int T, int H, int Dh) {
+    const int m = blockIdx.x, h = blockIdx.y;
+    const int b = m / T, n = m - b * T;
+    for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x)
+        Elem<BF>::st(qbuf, q_index<BF>(b, n, h, dim, H, Dh, T), q[(((size_t)m) * H + h) * Dh + dim]);
+}
+
+int launch_q_import(hydra_ctx *c, hipStream_t s, int B, const float *q_plain, void *qbuf) {
+    dim3 grid(B * c->tree.T, c->m.n_heads), block(64);
+    if (c->bf16) hipLaunchKernelGGL(q_import_kernel<true>, grid, block, 0, s, q_plain, (bf16_t *)qbuf, c->tree.T, c->m.n_heads, c->m.head_dim);
+    else         hipLaunchKernelGGL(q_import_kernel<false>, grid, block, 0, s, q_plain, (float *)qbuf, c->tree.T, c->m.n_heads, c->m.head_dim);
+    HYDRA_LAUNCH_CHECK("q_import_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// SwiGLU: act[m,f] = SiLU(gate[m,f]) * up[m,f].  The gate/up GEMM output holds
+// gate feature f in column (f / blk) * 2 blk + f % blk and up feature f `blk`
+// columns further (blk = 32 for the tile-interleaved bf16 weights, blk = F for
+// the fp32 family, where the rows are simply [gate ; up]).
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ void silu_mul_kernel(const float *part, int S, int part_ld, size_t split_stride, int F, int blk,
+                                typename Elem<BF>::type *out) {
+    const int m = blockIdx.y;
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= F) return;
+    const int gc = (f / blk) * 2 * blk + (f % blk);
+    const size_t row = (size_t)m * part_ld;
+    const float g = part_sum(part, S, split_stride, row + gc);
+    const float u = part_sum(part, S, split_stride, row + gc + blk);
+    Elem<BF>::st(out, x_index<BF>(m, f, F), silu_f(g) * u);
+}
+
+int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
+                    void *x_out, int M) {
+    const int F = c->m.ffn;
+    dim3 grid(ceil_div(F, 256), M), block(256);
+    if (c->bf16) hipLaunchKernelGGL(silu_mul_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, F, 32, (bf16_t *)x_out);
+    else         hipLaunchKernelGGL(silu_mul_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, F, F, (float *)x_out);
+    HYDRA_LAUNCH_CHECK("silu_mul_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// LM head epilogue: per row, logits = sum of split-K partials; greedy token =
+// lowest id among the maxima; margin = top-1 minus top-2 value.
+// ---------------------------------------------------------------------------
+struct Top2 { float v1; int i1; float v2; };
+__device__ __forceinline__ void top2_push(Top2 &t, float v, int i) {
+    if (v > t.v1 || (v == t.v1 && i < t.i1)) { t.v2 = t.v1; t.v1 = v; t.i1 = i; }
+    else if (v > t.v2) t.v2 = v;
+}
+__device__ __forceinline__ void top2_merge(Top2 &a, const Top2 &b) {
+    if (b.v1 > a.v1 || (b.v1 == a.v1 && b.i1 < a.i1)) { a.v2 = fmaxf(a.v1, b.v2); a.v1 = b.v1; a.i1 = b.i1; }
+    else a.v2 = fmaxf(a.v2, b.v1);
+}
+
+__global__ __launch_bounds__(256) void argmax_kernel(const float *part, int S, int part_ld, size_t split_stride, int V,
+                                                      int32_t *argmax, float *margin, float *logits) {
+    const int m = blockIdx.x;
+    Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
+    for (int v = threadIdx.x; v < V; v += 256) {
+        const float x = part_sum(part, S, split_stride, (size_t)m * part_ld + v);
+        if (logits) logits[(size_t)m * V + v] = x;
+        top2_push(t, x, v);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Top2 u = {__shfl_xor(t.v1, o, 64), __shfl_xor(t.i1, o, 64), __shfl_xor(t.v2, o, 64)};
+        top2_merge(t, u);
+    }
+    __shared__ Top2 red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Top2 r = red[0];
+        for (int w = 1; w < 4; ++w) top2_merge(r, red[w]);
+        argmax[m] = r.i1;
+        if (margin) margin[m] = r.v1 - r.v2;
+    }
+}
+
+int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, int M,
+                  int32_t *argmax, float *margin, float *logits) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, part, S, part_ld, split_stride, c->m.vocab, argmax, margin, logits);
+    HYDRA_LAUNCH_CHECK("argmax_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Plain [B][n_slots][2][H][Dh] fp32 <-> in-page cache placement (test harness).
+// ---------------------------------------------------------------------------
+template <bool BF, bool WRITE>
+__global__ void kv_plain_kernel(typename Elem<BF>::type *kpages, typename Elem<BF>::type *vpages,
+                                const int32_t *page_table, int max_pages, int n_pages, int layer, int first_slot,
+                                int n_slots, int H, int Dh, float *plain) {
+    const int b = blockIdx.z, i = blockIdx.x, h = blockIdx.y;
+    const int slot = first_slot + i;
+    const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
+    const int tok = slot & 15;
+    const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
+    float *pk = plain + ((((size_t)b * n_slots + i) * 2 + 0) * H + h) * Dh;
+    float *pv = plain + ((((size_t)b * n_slots + i) * 2 + 1) * H + h) * Dh;
+    for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x) {
+        if (WRITE) {
+            Elem<BF>::st(kpages, base + k_in_block<BF>(tok, dim, Dh), pk[dim]);
+            Elem<BF>::st(vpages, base + v_in_block<BF>(tok, dim, Dh), pv[dim]);
+        } else {
+            pk[dim] = Elem<BF>::ld(kpages, base + k_in_block<BF>(tok, dim, Dh));
+            pv[dim] = Elem<BF>::ld(vpages, base + v_in_block<BF>(tok, dim, Dh));
+        }
+    }
+}
+
+int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_kv *kv, int first_slot, int n_slots,
+                    float *plain, bool write_cache) {
+    dim3 grid(n_slots, c->m.n_heads, B), block(64);
+    const int H = c->m.n_heads, Dh = c->m.head_dim;
+#define KVP(BFv, Wv, TY)                                                                                             \
+    hipLaunchKernelGGL((kv_plain_kernel<BFv, Wv>), grid, block, 0, s, (TY *)kv->k_pages, (TY *)kv->v_pages,           \
+                       kv->page_table, kv->max_pages, kv->n_pages, layer, first_slot, n_slots, H, Dh, plain)
+    if (c->bf16) { if (write_cache) KVP(true, true, bf16_t); else KVP(true, false, bf16_t); }
+    else         { if (write_cache) KVP(false, true, float); else KVP(false, false, float); }
+#undef KVP
+    HYDRA_LAUNCH_CHECK("kv_plain_kernel");
+    return HYDRA_OK;
+}
+
+}  // namespace hydra

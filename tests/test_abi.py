@@ -1,0 +1,72 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header
+declares, and rejects bad descriptors on the host before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2402_05109_amd import binding as hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "hydra.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:int|size_t|const char \*)\s*\**\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_functions()
+    assert len(declared) >= 18
+    lib = hb.lib()
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in hydra.h but not exported"
+    assert sorted(hb.EXPORTS) == declared
+
+
+GOOD = dict(d=256, n_layers=2, n_heads=4, head_dim=64, ffn=688, vocab=1024, dtype=hb.HYDRA_F32, n_draft_heads=3,
+            parent=[-1, 0, 0, 1])
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(head_dim=63), hb.E_SHAPE), (dict(n_heads=8, head_dim=32), hb.E_UNSUPPORTED),
+    (dict(page_size=32), hb.E_UNSUPPORTED), (dict(dtype=7), hb.E_INVALID_ARG), (dict(vocab=1), hb.E_INVALID_ARG),
+    (dict(parent=[0, 0]), hb.E_SHAPE), (dict(parent=[-1, 0, 1, 0]), hb.E_SHAPE), (dict(parent=[-1, 1]), hb.E_SHAPE),
+    (dict(parent=[-1] + [0] * 128), hb.E_UNSUPPORTED), (dict(parent=[-1] + [0] * 33), hb.E_UNSUPPORTED),
+    (dict(n_draft_heads=9), hb.E_UNSUPPORTED), (dict(mlp_layers=0), hb.E_UNSUPPORTED), (dict(max_batch=0), hb.E_INVALID_ARG),
+    (dict(dtype=hb.HYDRA_BF16), hb.E_UNSUPPORTED),          # ffn 688 is not a multiple of 128
+])
+def test_create_rejects_bad_descriptors(change, code):
+    kw = dict(GOOD); kw.update(change)
+    with pytest.raises(hb.HydraError) as e:
+        hb.Hydra(**kw)
+    assert e.value.code == code and hb.last_error()
+
+
+def test_sizes_and_tree_depth_without_a_device():
+    h = hb.Hydra(**GOOD)
+    assert h.depth == 2
+    d, F, V = 256, 688, 1024
+    weights = 4 * (2 * V * d + 2 * (4 * d * d + 3 * d * F) + (2 + 3 + 4) * d * d + 3 * V * d)
+    assert weights <= h.weights_bytes() <= weights + (1 << 20) + 4 * 8192 * 32 * 2
+    assert h.workspace_bytes(1) > 0 and h.workspace_bytes(2) == 0      # max_batch = 1
+    big = hb.Hydra(d=4096, n_layers=32, n_heads=32, head_dim=128, ffn=11008, vocab=32000, dtype=hb.HYDRA_BF16,
+                   n_draft_heads=4, parent=[-1] + [0] * 5)
+    n = 2 * (32 * (4 * 4096 ** 2 + 3 * 4096 * 11008) + 2 * 32000 * 4096 + sum((i + 1) * 4096 ** 2 + 32000 * 4096 for i in range(1, 5)))
+    assert n <= big.weights_bytes() <= n * 1.001 + (1 << 24)
+
+
+def test_calls_without_bound_weights_fail_cleanly():
+    h = hb.Hydra(**GOOD)
+    lib = hb.lib()
+    buf = C.create_string_buffer(512)
+    ws = (C.addressof(buf) + 255) // 256 * 256
+    rc = lib.hydra_draft_tree(h._h, None, 1, ws, ws, ws, ws)
+    assert rc == hb.E_STATE
+    assert lib.hydra_draft_tree(h._h, None, 2, ws, ws, ws, ws) == hb.E_CAPACITY
+    assert lib.hydra_draft_tree(None, None, 1, ws, ws, ws, ws) == hb.E_INVALID_ARG
+    assert lib.accept_greedy(h._h, None, 1, None, None, None, None, None, None) in (hb.E_STATE, hb.E_INVALID_ARG)
+    assert lib.hydra_load_tensor(h._h, None, 99, 0, 0, ws) == hb.E_STATE
