@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the Hydra-decoding hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A "step" is one pass of the whole hot path over the batch:
+hydra_draft_tree -> tree_verify_forward -> accept_greedy -> kv_compact.
+The workload is seeded and synthetic (random-init weights of the named shape,
+uniform random prompt); with random heads the natural acceptance length is
+about one token per step, so tokens/s is close to steps/s.
+
+Prints ONE JSON line.  `value` is generated tokens per second of the decode loop
+with everything resident in HBM.  `roofline` describes the dominant kernel (the
+weight-streaming GEMM): algorithmic weight bytes per launch over the HIP-event
+duration of the launch.  `cpu_baseline` is the CPU oracle timed on this host on
+a bounded sample (see `sample`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+
+def verify_bytes(cfg, B, L, T):
+    """Algorithmic HBM bytes of one tree_verify_forward: every base weight once, the
+    cached K/V of the context once, the new K/V written, the token activations."""
+    e = 2 if cfg.dtype == "bf16" else 4
+    w = e * (cfg.NL * (4 * cfg.d * cfg.d + 3 * cfg.d * cfg.F) + cfg.d * cfg.V)
+    kvtok = 2 * cfg.d * cfg.NL * e
+    return w + B * ((L + T) * kvtok + T * kvtok) + e * B * T * cfg.d
+
+
+def draft_bytes(cfg):
+    e = 2 if cfg.dtype == "bf16" else 4
+    tot = 0
+    for i in range(1, cfg.K + 1):
+        tot += e * ((i + 1) * cfg.d * cfg.d + (cfg.mlp_layers - 1) * cfg.d * cfg.d + cfg.d * cfg.V)
+    return tot
+
+
+def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu):
+    """Oracle on the host cores: one Hydra step (draft + verify) of the same shape with
+    `n_layers_sample` of the NL decoder layers, layer time scaled to NL."""
+    from oracle import hydra_oracle as O
+    tree = O.Tree(parent)
+    names = ["embed", "lm_head", "final_norm"]
+    for l in range(n_layers_sample):
+        names += [f"layers.{l}.{t}" for t in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
+    for i in range(1, cfg.K + 1):
+        names += [f"heads.{i}.w1", f"heads.{i}.b1", f"heads.{i}.wout"]
+        for j in range(2, cfg.mlp_layers + 1):
+            names += [f"heads.{i}.w{j}", f"heads.{i}.b{j}"]
+    W = {n: get_cpu(n) for n in names}
+    m = O.Model(cfg.d, n_layers_sample, cfg.H, cfg.Dh, cfg.F, cfg.V, cfg.K, cfg.mlp_layers, W,
+                rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, include_root_embedding=cfg.include_root_embedding)
+    rng = np.random.default_rng(0)
+    cache = O.FlatCache(m, L + tree.T)
+    cache.K[:, :L] = rng.standard_normal(cache.K[:, :L].shape) * 0.5
+    cache.V[:, :L] = rng.standard_normal(cache.V[:, :L].shape) * 0.5
+    h = rng.standard_normal(cfg.d)
+    t0 = time.perf_counter()
+    tok, _ = O.draft_tree(m, tree, h, 1)
+    t_draft = time.perf_counter() - t0
+    # time the LM head + embedding part separately by a zero-layer model
+    m0 = O.Model(cfg.d, 0, cfg.H, cfg.Dh, cfg.F, cfg.V, cfg.K, cfg.mlp_layers, W, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+    t0 = time.perf_counter()
+    O.tree_verify(m0, O.FlatCache(m0, L + tree.T), L, tree, tok)
+    t_head = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.tree_verify(m, cache, L, tree, tok)
+    t_verify_s = time.perf_counter() - t0
+    per_layer = max(t_verify_s - t_head, 0.0) / n_layers_sample
+    t_step = t_draft + t_head + per_layer * cfg.NL
+    return t_step, t_draft + t_head + t_verify_s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by batch row with no collectives; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor, uniform_tokens
+    from paper_2402_05109_amd.session import Session
+
+    cfg = CONFIGS[args.config]
+    if args.layers:
+        cfg = cfg.with_(NL=args.layers)
+    tree_name = {16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T]
+    parent = frozen_tree(tree_name)
+    B, L0 = cfg.batch[0], cfg.prompt[0]
+    spec = WeightSpec(cfg)
+    dev = "cuda:0"
+    max_len = L0 + (args.steps + args.warmup + 8) * (cfg.K + 1)
+    sess = Session(cfg, parent, B, max_len, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=128)
+    prompts = torch.stack([uniform_tokens(cfg.seed, b, L0, cfg.V) for b in range(B)])
+    sess.prefill(prompts)
+    torch.cuda.synchronize()
+
+    o = sess.out()
+    acc_log = torch.zeros(args.steps, B, dtype=torch.int32, device=dev)
+    for _ in range(args.warmup):
+        sess.step()
+    sess.sync_len()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        sess.step()
+        acc_log[i].copy_(o.n_acc)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tokens = int(acc_log.sum().item())
+    flags = sess.main.read_flags()
+    L_end = sess.sync_len()
+
+    # per-call latencies at the end-of-run context length (seq_len restored after each step)
+    def timed(fn, reps=20):
+        saved = (sess.seq_len.clone(), sess.h_last.clone(), sess.root.clone(), sess.host_len)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(reps):
+            ev0.record(); fn(); ev1.record(); ev1.synchronize()
+            ts.append(ev0.elapsed_time(ev1))
+            sess.seq_len.copy_(saved[0]); sess.h_last.copy_(saved[1]); sess.root.copy_(saved[2]); sess.host_len = saved[3]
+        return float(np.median(ts))
+
+    t_draft = timed(sess.draft)
+    t_verify = timed(sess.verify)
+    t_tail = timed(lambda: (sess.accept(), sess.compact()))
+    vb = verify_bytes(cfg, B, L_end, cfg.T)
+
+    # dominant kernel: HIP events around every GEMM launch of a few whole steps
+    sess.main.profile_begin()
+    saved = (sess.seq_len.clone(), sess.h_last.clone(), sess.root.clone(), sess.host_len)
+    for _ in range(4):
+        sess.step()
+    n_launch, ms_sum, w_bytes = sess.main.profile_end()
+    sess.seq_len.copy_(saved[0]); sess.h_last.copy_(saved[1]); sess.root.copy_(saved[2]); sess.host_len = saved[3]
+    peak = 8000.0
+    ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
+
+    # autoregressive baseline with the same kernels (one-node tree)
+    sess.ctx("ar")
+    t_ar = timed(lambda: sess.step("ar"))
+
+    out = {
+        "metric": "generated tokens/s at batch 1, 7B shape; verify-step HBM GB/s vs peak" if args.config == 2 else f"generated tokens/s, config {args.config}",
+        "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg.name} shape d={cfg.d} NL={cfg.NL} H={cfg.H}x{cfg.Dh} F={cfg.F} V={cfg.V}, "
+                               f"{cfg.K} Hydra heads x {cfg.mlp_layers}-layer MLP, tree {tree_name} (T={cfg.T}), B={B}, "
+                               f"prompt {L0} uniform tokens, paged KV (16), natural acceptance",
+                   "tokens_generated": tokens, "mean_acceptance": tokens / (args.steps * B), "context_at_end": L_end,
+                   "device_flags": flags},
+        "verify": {"ms": t_verify, "algorithmic_GB": vb / 1e9, "GBps": vb / (t_verify * 1e-3) / 1e9,
+                   "frac_of_8TBps": vb / (t_verify * 1e-3) / 8e12, "context": L_end},
+        "draft": {"ms": t_draft, "algorithmic_GB": draft_bytes(cfg) / 1e9, "GBps": draft_bytes(cfg) / (t_draft * 1e-3) / 1e9},
+        "accept_compact_ms": t_tail,
+        "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
+        "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",
+                     "achieved": ach, "peak": peak, "unit": "GB/s", "frac": ach / peak, "traffic": None,
+                     "launches_timed": n_launch, "avg_launch_us": ms_sum / max(n_launch, 1) * 1e3,
+                     "avg_weight_MB_per_launch": w_bytes / max(n_launch, 1) / 1e6},
+    }
+    if not args.no_cpu_baseline:
+        ns = min(2, cfg.NL)
+        cores = os.cpu_count() or 1
+        try:
+            import threadpoolctl
+            info = threadpoolctl.threadpool_info()
+            cores = max([i.get("num_threads", 1) for i in info] + [1])
+        except Exception:
+            pass
+        cpu = lambda n: make_tensor(spec, n, device=dev).cpu()
+        t_step, t_spent = cpu_baseline(cfg, parent, L0, ns, cpu)
+        out["cpu_baseline"] = {"value": B / t_step, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": f"one Hydra step (all {cfg.K} draft heads, LM head, T={cfg.T} tree, context {L0}) with "
+                                         f"{ns} of {cfg.NL} decoder layers timed ({t_spent:.1f} s of CPU work) and the per-layer time "
+                                         f"scaled to {cfg.NL} layers; acceptance 1 token/step"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
