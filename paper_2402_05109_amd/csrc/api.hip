@@ -118,7 +118,7 @@ WsLayout ws_layout(const hydra_ctx *c, int B) {
     // split-K partial sums: the largest S * Mpad * Npad over every GEMM this context can launch
     size_t part = 0;
     auto need = [&](size_t m, size_t n, size_t k) {
-        GemmPlan p = plan_gemm(c, (int)m, (int)n, (int)k);
+        GemmPlan p = plan_gemm(c, (int)m, (int)n, (int)k, false, true);
         const size_t mp = align_up(m, 32), np = (size_t)gemm_npad(c, (int)n);
         part = std::max(part, (size_t)p.splits * mp * np * 4);
     };
@@ -135,6 +135,7 @@ WsLayout ws_layout(const hydra_ctx *c, int B) {
     const size_t rec = Tq * c->m.head_dim + 2 * Tq;
     w.apart = off; off += c->bf16 ? align_up((size_t)B * c->m.n_heads * w.attn_units * rec * 4, 256) : 256;
     w.z = off;     off += align_up(std::max<size_t>(Md, 1) * d * 4, 256);
+    w.ss = off;    off += align_up((d / 32 + 1) * rows * 4, 256);
     w.total = off;
     return w;
 }
@@ -246,6 +247,11 @@ int hydra_bind_weights(hydra_ctx *c, void *stream, void *arena, int table_slot) 
     HYDRA_HIP(hipMemcpyAsync(slot, &c->tree, sizeof(TreeDev), hipMemcpyHostToDevice, s));
     HYDRA_HIP(hipMemcpyAsync(c->arena + c->off_rope, c->rope.data(), c->rope.size() * 4, hipMemcpyHostToDevice, s));
     HYDRA_HIP(hipStreamSynchronize(s));     // host buffers may change after return
+    if (c->bf16) {
+        int rc = gemm_max_dynamic_lds(c);
+        if (rc) return rc;
+        if ((rc = attn_max_dynamic_lds(c))) return rc;
+    }
     return HYDRA_OK;
 }
 
@@ -344,14 +350,23 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
         const int Kin = head_in_width(c, i);
         GemmPlan p;
         if ((rc = launch_draft_gather(c, s, B, i, h_last, tree_tokens, xa, flags_ptr(c)))) return rc;
-        if ((rc = launch_gemm(c, s, xa, A + c->head[i].w1, part, Mi, d, Kin, &p))) return rc;
-        size_t ss = (size_t)align_up(Mi, 32) * gemm_npad(c, d);
-        if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].b1), z, false, xb, Mi))) return rc;
         void *cur = xb, *other = xa;
-        for (int j = 2; j <= c->h.mlp_layers; ++j) {
-            if ((rc = launch_gemm(c, s, cur, A + c->head[i].wl[j - 2], part, Mi, d, d, &p))) return rc;
-            if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].bl[j - 2]), z, true, other, Mi))) return rc;
-            std::swap(cur, other);
+        if (c->bf16) {
+            // MLP layers with bias + SiLU (+ residual) fused into the GEMM epilogue
+            if ((rc = launch_gemm_bias_silu(c, s, xa, A + c->head[i].w1, Mi, d, Kin, (const float *)(A + c->head[i].b1), z, false, xb))) return rc;
+            for (int j = 2; j <= c->h.mlp_layers; ++j) {
+                if ((rc = launch_gemm_bias_silu(c, s, cur, A + c->head[i].wl[j - 2], Mi, d, d, (const float *)(A + c->head[i].bl[j - 2]), z, true, other))) return rc;
+                std::swap(cur, other);
+            }
+        } else {
+            if ((rc = launch_gemm(c, s, xa, A + c->head[i].w1, part, Mi, d, Kin, &p))) return rc;
+            const size_t ss = (size_t)align_up(Mi, 32) * gemm_npad(c, d);
+            if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].b1), z, false, xb, Mi))) return rc;
+            for (int j = 2; j <= c->h.mlp_layers; ++j) {
+                if ((rc = launch_gemm(c, s, cur, A + c->head[i].wl[j - 2], part, Mi, d, d, &p))) return rc;
+                if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].bl[j - 2]), z, true, other, Mi))) return rc;
+                std::swap(cur, other);
+            }
         }
         if ((rc = launch_gemm(c, s, cur, A + c->head[i].wout, part, Mi, V, d, &p))) return rc;
         const size_t sv = (size_t)align_up(Mi, 32) * gemm_npad(c, V);
@@ -380,13 +395,36 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
     const size_t mp = align_up(M, 32);
     const int ld_d = gemm_npad(c, d), ld_qkv = gemm_npad(c, 3 * d), ld_gu = gemm_npad(c, 2 * F), ld_v = gemm_npad(c, V);
     GemmPlan p;
+    const RowScale none = {nullptr, 0, 0, 0, 0.f};
+    if (c->bf16) {
+        // Fused flow.  The residual epilogues leave x, xg = bf16(x * gain of the next norm) and per-band sums of
+        // squares; the 1/rms factor of each RMSNorm is applied by the consumer of the following GEMM.
+        float *ss = (float *)(W + w.ss);
+        const int Mpad = (int)align_up(std::max<size_t>(M, 1), 128);
+        const RowScale rs = {ss, d / 32, Mpad, d, c->m.rms_eps};
+        if ((rc = launch_embed_prep(c, s, tree_tokens, x, (const float *)(A + c->layer[0].attn_norm), xa, ss, Mpad, M, flags))) return rc;
+        for (int l = 0; l < c->m.n_layers; ++l) {
+            const LayerOff &o = c->layer[l];
+            const float *next_gain = (const float *)(A + (l + 1 < c->m.n_layers ? c->layer[l + 1].attn_norm : c->off_final_norm));
+            if ((rc = launch_gemm(c, s, xa, A + o.wqkv, part, M, 3 * d, d, &p))) return rc;
+            if ((rc = launch_rope_append(c, s, part, p.splits, ld_qkv, mp * ld_qkv, rs, B, l, seq_len, kv, qbuf, flags))) return rc;
+            if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xb, nullptr, flags))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad))) return rc;
+            if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, d / 32, Mpad, xb))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad))) return rc;
+        }
+        if ((rc = launch_final_hidden(c, s, x, (const float *)(A + c->off_final_norm), rs, hidden, M))) return rc;
+        if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;
+        if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rs, M, argmax, margin, logits))) return rc;
+        return HYDRA_OK;
+    }
     if ((rc = launch_embed(c, s, tree_tokens, x, M, flags))) return rc;
     int S_prev = 0;                         // split-K partials of the previous residual branch, still to be added to x
     for (int l = 0; l < c->m.n_layers; ++l) {
         const LayerOff &o = c->layer[l];
         if ((rc = launch_rmsnorm(c, s, x, part, S_prev, ld_d, mp * ld_d, (const float *)(A + o.attn_norm), xa, M, nullptr))) return rc;
         if ((rc = launch_gemm(c, s, xa, A + o.wqkv, part, M, 3 * d, d, &p))) return rc;
-        if ((rc = launch_rope_append(c, s, part, p.splits, ld_qkv, mp * ld_qkv, B, l, seq_len, kv, qbuf, flags))) return rc;
+        if ((rc = launch_rope_append(c, s, part, p.splits, ld_qkv, mp * ld_qkv, none, B, l, seq_len, kv, qbuf, flags))) return rc;
         if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xa, nullptr, flags))) return rc;
         if ((rc = launch_gemm(c, s, xa, A + o.wo, part, M, d, d, &p))) return rc;
         if ((rc = launch_rmsnorm(c, s, x, part, p.splits, ld_d, mp * ld_d, (const float *)(A + o.ffn_norm), xa, M, nullptr))) return rc;
@@ -397,7 +435,7 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
     }
     if ((rc = launch_rmsnorm(c, s, x, part, S_prev, ld_d, mp * ld_d, (const float *)(A + c->off_final_norm), xa, M, hidden))) return rc;
     if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;
-    if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, M, argmax, margin, logits))) return rc;
+    if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, none, M, argmax, margin, logits))) return rc;
     return HYDRA_OK;
 }
 

@@ -1,5 +1,4 @@
-// bf16 storage family: tree attention on MFMA with split-KV, and the merge of
-// the split results.
+// bf16 storage family: tree attention on MFMA.
 //
 // Per (row b, head h) the T tree queries attend to slots [0, L) of the paged
 // cache and to the tree slots allowed by each query's ancestor bitmask (paper,
@@ -12,13 +11,18 @@
 // Working with the transposes makes a query a COLUMN of every accumulator, so
 // its softmax statistics, its ancestor mask and its rescale factor are per-lane
 // scalars, and the exponentiated scores are already in the register order the
-// second contraction needs for its B operand: no LDS, no shuffles except one
-// exchange between the two half-waves.  The in-page placement of K and V (see
-// device_common.h) is chosen so that both A operands are single coalesced
+// second contraction needs for its B operand: no LDS and no shuffles in the
+// loop except one exchange between the two half-waves.  The in-page placement
+// of K and V (device_common.h) makes both A operands single coalesced
 // 16-byte-per-lane loads straight from the cache pages.
 //
-// A wave is one "unit": it walks 32-key tiles unit, unit + U, ... of one
-// (b, h, query group) and leaves (max, sum, O) for attn_merge_kernel.
+// A workgroup is 8 waves on one (b, h): QW of them take different 32-query
+// tiles, and for each query tile 8/QW waves split the keys (32-key tiles taken
+// round-robin, next tile prefetched while the current one is multiplied).  The
+// key-split waves are merged through LDS.  With one workgroup per (b, h)
+// (gridDim.x == 1) the result goes straight out as the next GEMM's input;
+// longer contexts use several workgroups and leave (max, sum, O) records that
+// attn_merge_kernel combines.
 #include "device_common.h"
 #include "internal.h"
 
@@ -27,110 +31,110 @@ namespace hydra {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 
-// record of one unit in the partial buffer: O[Tq][Dh], m[Tq], l[Tq]   (Tq = 32 * ceil(T/32))
+// record of one workgroup in the partial buffer: O[Tq][Dh], m[Tq], l[Tq]   (Tq = 32 * ceil(T/32))
 __host__ __device__ inline size_t apart_record(int Tq, int Dh) { return (size_t)Tq * Dh + 2 * (size_t)Tq; }
 
-template <int QT, int DH>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const u32x4_t *__restrict__ qbuf,
-                                                         const bf16_t *__restrict__ kpages,
-                                                         const bf16_t *__restrict__ vpages,
-                                                         const int32_t *__restrict__ page_table, int max_pages,
-                                                         int n_pages, int layer, const int32_t *__restrict__ seq_len,
-                                                         const TreeDev *__restrict__ tree, int H, int units, int QG,
-                                                         float scale, float *__restrict__ apart, int32_t *flags) {
-    constexpr int KS = DH / 16;      // k-steps of the score contraction
-    constexpr int DT = DH / 32;      // 32-row bands of O^T
+enum { ATTN_WAVES = 8 };
+
+template <int DH>
+struct KVTile { u32x4_t k[DH / 16]; u32x4_t v[2][DH / 32]; };
+
+template <int DH>
+__device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const bf16_t *kpages, const bf16_t *vpages,
+                                             const int32_t *pt, int t, int row_pages, int layer, int n_pages, int H,
+                                             int h, int lane) {
+    const int hl = lane >> 5, col = lane & 31;
+    const int p0 = pt[2 * t];
+    const int p1 = (2 * t + 1 < row_pages) ? pt[2 * t + 1] : p0;
+    const u32x4_t *kp = reinterpret_cast<const u32x4_t *>(kpages + kv_block_base(layer, n_pages, (col >> 4) ? p1 : p0, H, h, DH));
+#pragma unroll
+    for (int s = 0; s < DH / 16; ++s) kv.k[s] = kp[(2 * s + hl) * 16 + (col & 15)];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const u32x4_t *vp = reinterpret_cast<const u32x4_t *>(vpages + kv_block_base(layer, n_pages, g ? p1 : p0, H, h, DH));
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt) kv.v[g][dt] = vp[(32 * dt + col) * 2 + hl];
+    }
+}
+
+template <int DH, bool PACKED>
+__global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
+    const u32x4_t *__restrict__ qbuf, const bf16_t *__restrict__ kpages, const bf16_t *__restrict__ vpages,
+    const int32_t *__restrict__ page_table, int max_pages, int n_pages, int layer, const int32_t *__restrict__ seq_len,
+    const TreeDev *__restrict__ tree, int H, int QW, float scale, float *__restrict__ apart, void *out,
+    int32_t *flags) {
+    constexpr int KS = DH / 16, DT = DH / 32;
+    extern __shared__ float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int unit = blockIdx.x * 4 + wave;
-    const int h = blockIdx.y;
-    const int b = blockIdx.z / QG, qg = blockIdx.z - b * QG;
+    const int hl = lane >> 5, col = lane & 31;
+    const int KWV = ATTN_WAVES / QW;
+    const int qw = wave % QW, kwv = wave / QW;
+    const int h = blockIdx.y, b = blockIdx.z;
     const int T = tree->T;
     const int QTtot = (T + 31) >> 5;
+    const int Tq = QTtot * 32;
     const int L = seq_len[b];
-    if (L < 0 || L + T > max_pages * 16) {
+    if (L < 0 || L + T > max_pages * 16) {                 // uniform over the workgroup
         if (threadIdx.x == 0 && blockIdx.x == 0 && h == 0) atomicOr(flags, FLAG_CAPACITY);
         return;
     }
     const int total = L + T;
     const int n_tiles = (total + 31) >> 5;
     const int row_pages = (total + 15) >> 4;
-    if (unit >= units || unit >= n_tiles) return;
-
-    const int hl = lane >> 5, col = lane & 31;
-    // Q^T operands and this lane's ancestor masks
-    u32x4_t qreg[QT][KS];
-    uint64_t anc0[QT], anc1[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int qtile = min(qg * QT + qt, QTtot - 1);
-        const size_t blk = (((size_t)b * H + h) * QTtot + qtile) * KS;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[qt][s] = qbuf[(blk + s) * 64 + lane];
-        const int query = (qg * QT + qt) * 32 + col;
-        anc0[qt] = query < T ? tree->anc[query][0] : 0ull;
-        anc1[qt] = query < T ? tree->anc[query][1] : 0ull;
-    }
-    f32x16_t o[QT][DT];
-    float m_run[QT], l_run[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        m_run[qt] = -INFINITY;
-        l_run[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[qt][dt][v] = 0.f;
-    }
+    const int units = gridDim.x * KWV;
+    const int unit = blockIdx.x * KWV + kwv;
+    const bool active = qw < QTtot;                        // idle waves only take part in the barriers
     const int32_t *pt = page_table + (size_t)b * max_pages;
 
-    for (int t = unit; t < n_tiles; t += units) {
-        const int slot0 = t * 32;
-        const bool page1_ok = 2 * t + 1 < row_pages;
-        const int p0 = pt[2 * t];
-        const int p1 = page1_ok ? pt[2 * t + 1] : p0;
-        // ---- K tile: lane's key is col (page col/16, token col%16), half hl of every 16-dim step
-        const int kpage = (col >> 4) ? p1 : p0;
-        const u32x4_t *kp = reinterpret_cast<const u32x4_t *>(kpages + kv_block_base(layer, n_pages, kpage, H, h, DH));
-        u32x4_t kreg[KS];
+    f32x16_t o[DT];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) kreg[s] = kp[(2 * s + hl) * 16 + (col & 15)];
-        // ---- V^T tiles: per page g and band dt, lane's dim is 32 dt + col, key half hl
-        u32x4_t vreg[2][DT];
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            const u32x4_t *vp = reinterpret_cast<const u32x4_t *>(vpages + kv_block_base(layer, n_pages, g ? p1 : p0, H, h, DH));
+        for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    if (active && unit < n_tiles) {
+        u32x4_t qreg[KS];
+        const size_t blk = (((size_t)b * H + h) * QTtot + qw) * KS;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) vreg[g][dt] = vp[(32 * dt + col) * 2 + hl];
-        }
-        const bool tail = slot0 + 32 > total;
-        if (tail) {     // zero V entries of slots >= total (stale or never written), so 0 * garbage cannot appear
+        for (int s = 0; s < KS; ++s) qreg[s] = qbuf[(blk + s) * 64 + lane];
+        const int query = qw * 32 + col;
+        const uint64_t anc0 = query < T ? tree->anc[query][0] : 0ull;
+        const uint64_t anc1 = query < T ? tree->anc[query][1] : 0ull;
+
+        KVTile<DH> cur, nxt;
+        load_kv_tile<DH>(cur, kpages, vpages, pt, unit, row_pages, layer, n_pages, H, h, lane);
+        for (int t = unit; t < n_tiles; t += units) {
+            const bool more = t + units < n_tiles;
+            if (more) load_kv_tile<DH>(nxt, kpages, vpages, pt, t + units, row_pages, layer, n_pages, H, h, lane);
+            const int slot0 = t * 32;
+            if (slot0 + 32 > total) {   // zero V of slots >= total (stale or never written): 0 * garbage must not appear
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
+                for (int g = 0; g < 2; ++g)
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    // dword w holds keys i = 2w, 2w+1 of this half: token = 8*(i/4) + 4*hl + i%4
-                    const int i0 = 2 * w, i1 = 2 * w + 1;
-                    const int s0 = slot0 + 16 * g + 8 * (i0 >> 2) + 4 * hl + (i0 & 3);
-                    const int s1 = slot0 + 16 * g + 8 * (i1 >> 2) + 4 * hl + (i1 & 3);
-                    const uint32_t keep = (s0 < total ? 0x0000ffffu : 0u) | (s1 < total ? 0xffff0000u : 0u);
+                    for (int w = 0; w < 4; ++w) {
+                        // dword w holds keys i = 2w, 2w+1 of this half-wave: token = 8*(i/4) + 4*hl + i%4
+                        const int i0 = 2 * w, i1 = 2 * w + 1;
+                        const int s0 = slot0 + 16 * g + 8 * (i0 >> 2) + 4 * hl + (i0 & 3);
+                        const int s1 = slot0 + 16 * g + 8 * (i1 >> 2) + 4 * hl + (i1 & 3);
+                        const uint32_t keep = (s0 < total ? 0x0000ffffu : 0u) | (s1 < total ? 0xffff0000u : 0u);
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) vreg[g][dt][w] &= keep;
-                }
-        }
-        const bool need_mask = slot0 + 32 > L;
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
+                        for (int dt = 0; dt < DT; ++dt) cur.v[g][dt][w] &= keep;
+                    }
+            }
             f32x16_t sc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) sc[v] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kreg[s]),
-                                                            __builtin_bit_cast(bf16x8_t, qreg[qt][s]), sc, 0, 0, 0);
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.k[s]),
+                                                            __builtin_bit_cast(bf16x8_t, qreg[s]), sc, 0, 0, 0);
+            const bool need_mask = slot0 + 32 > L;
             float cmax = -INFINITY;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const u32x4_t *__restric
                     bool ok = slot < L;
                     if (!ok) {
                         const int a = slot - L;
-                        ok = a < T && (((a < 64 ? anc0[qt] >> a : anc1[qt] >> (a - 64)) & 1ull) != 0);
+                        ok = a < T && (((a < 64 ? anc0 >> a : anc1 >> (a - 64)) & 1ull) != 0);
                     }
                     x = ok ? x : -INFINITY;
                 }
@@ -148,9 +152,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const u32x4_t *__restric
                 cmax = fmaxf(cmax, x);
             }
             cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
-            const float m_new = fmaxf(m_run[qt], cmax);
+            const float m_new = fmaxf(m_run, cmax);
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __expf(m_run[qt] - m_safe);
+            const float alpha = __expf(m_run - m_safe);
             float rs = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -159,12 +163,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const u32x4_t *__restric
                 rs += p;
             }
             rs += __shfl_xor(rs, 32, 64);
-            l_run[qt] = l_run[qt] * alpha + rs;
-            m_run[qt] = m_new;
+            l_run = l_run * alpha + rs;
+            m_run = m_new;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[qt][dt][v] *= alpha;
+                for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
             // P^T operands: page g uses accumulator registers 8g .. 8g+7 in order
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
@@ -173,29 +177,76 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const u32x4_t *__restric
                 for (int w = 0; w < 4; ++w) pb[w] = pack2bf(sc[8 * g + 2 * w], sc[8 * g + 2 * w + 1]);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
-                    o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vreg[g][dt]),
-                                                                       __builtin_bit_cast(bf16x8_t, pb), o[qt][dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.v[g][dt]),
+                                                                   __builtin_bit_cast(bf16x8_t, pb), o[dt], 0, 0, 0);
             }
+            if (more) cur = nxt;
         }
     }
-    // ---- leave (O, m, l) of this unit
-    const int Tq = QTtot * 32;
-    float *rec = apart + ((((size_t)b * H + h) * units) + unit) * apart_record(Tq, DH);
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int query = (qg * QT + qt) * 32 + col;
-        if (query >= Tq) continue;
+
+    // ---- merge the KWV key-split waves of each query tile through LDS
+    // layout: ml[QW][KWV][2][32] then O[QW][KWV][DT*16][64]
+    float *ml = lds;
+    float *ob = lds + ATTN_WAVES * 64;
+    if (hl == 0) {
+        ml[((qw * KWV + kwv) * 2 + 0) * 32 + col] = m_run;
+        ml[((qw * KWV + kwv) * 2 + 1) * 32 + col] = l_run;
+    }
+    __syncthreads();
+    float m_tot = -INFINITY;
+    for (int w = 0; w < KWV; ++w) m_tot = fmaxf(m_tot, ml[((qw * KWV + w) * 2 + 0) * 32 + col]);
+    float l_tot = 0.f;
+    for (int w = 0; w < KWV; ++w) {
+        const float mw = ml[((qw * KWV + w) * 2 + 0) * 32 + col];
+        l_tot += __expf(mw - (m_tot == -INFINITY ? 0.f : m_tot)) * ml[((qw * KWV + w) * 2 + 1) * 32 + col];
+    }
+    const float mine = __expf(m_run - (m_tot == -INFINITY ? 0.f : m_tot));
+    {
+        float *dst = ob + (size_t)(qw * KWV + kwv) * DT * 16 * 64 + lane;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                f32x4_t v4 = {o[qt][dt][4 * g4], o[qt][dt][4 * g4 + 1], o[qt][dt][4 * g4 + 2], o[qt][dt][4 * g4 + 3]};
-                *reinterpret_cast<f32x4_t *>(rec + (size_t)query * DH + 32 * dt + 8 * g4 + 4 * hl) = v4;
-            }
-        if (hl == 0) {
-            rec[(size_t)Tq * DH + query] = m_run[qt];
-            rec[(size_t)Tq * DH + Tq + query] = l_run[qt];
+            for (int v = 0; v < 16; ++v) dst[(dt * 16 + v) * 64] = o[dt][v] * mine;
+    }
+    __syncthreads();
+    if (!active) return;
+    // wave kwv finishes bands dt = kwv, kwv + KWV, ...
+    const int query = qw * 32 + col;
+    const bool final_out = gridDim.x == 1;
+    const float inv = final_out ? 1.0f / l_tot : 1.0f;
+    float *rec = apart + ((((size_t)b * H + h) * gridDim.x) + blockIdx.x) * apart_record(Tq, DH);
+    for (int dt = kwv; dt < DT; dt += KWV) {
+        float acc[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        for (int w = 0; w < KWV; ++w) {
+            const float *src = ob + (size_t)(qw * KWV + w) * DT * 16 * 64 + lane;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] += src[(dt * 16 + v) * 64];
         }
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int dim = 32 * dt + 8 * g4 + 4 * hl;          // 4 consecutive dims: registers 4*g4 .. 4*g4+3
+            if (final_out) {
+                if (query < T) {
+                    const int m = b * T + query;
+                    if (PACKED) {
+                        u32x2_t pk = {pack2bf(acc[4 * g4] * inv, acc[4 * g4 + 1] * inv), pack2bf(acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv)};
+                        *reinterpret_cast<u32x2_t *>(reinterpret_cast<bf16_t *>(out) + x_index<true>(m, h * DH + dim, H * DH)) = pk;
+                    } else {
+                        f32x4_t v4 = {acc[4 * g4] * inv, acc[4 * g4 + 1] * inv, acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv};
+                        *reinterpret_cast<f32x4_t *>(reinterpret_cast<float *>(out) + ((size_t)m * H + h) * DH + dim) = v4;
+                    }
+                }
+            } else {
+                f32x4_t v4 = {acc[4 * g4], acc[4 * g4 + 1], acc[4 * g4 + 2], acc[4 * g4 + 3]};
+                *reinterpret_cast<f32x4_t *>(rec + (size_t)query * DH + dim) = v4;
+            }
+        }
+    }
+    if (!final_out && kwv == 0 && hl == 0) {
+        rec[(size_t)Tq * DH + query] = m_tot;
+        rec[(size_t)Tq * DH + Tq + query] = l_tot;
     }
 }
 
@@ -206,22 +257,20 @@ __global__ void attn_merge_kernel(const float *__restrict__ apart, const int32_t
     const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int L = seq_len[b];
     if (L < 0 || L + T > max_pages * 16) return;
-    const int n_tiles = (L + T + 31) >> 5;
-    const int nu = min(units, n_tiles);
     const int Tq = ((T + 31) >> 5) * 32;
     const size_t recsz = apart_record(Tq, Dh);
     const float *base = apart + (((size_t)b * H + h) * units) * recsz;
     float mt = -INFINITY;
-    for (int u = 0; u < nu; ++u) mt = fmaxf(mt, base[u * recsz + (size_t)Tq * Dh + n]);
+    for (int u = 0; u < units; ++u) mt = fmaxf(mt, base[u * recsz + (size_t)Tq * Dh + n]);
     float den = 0.f;
-    for (int u = 0; u < nu; ++u) {
+    for (int u = 0; u < units; ++u) {
         const float *r = base + u * recsz;
         den += __expf(r[(size_t)Tq * Dh + n] - mt) * r[(size_t)Tq * Dh + Tq + n];
     }
     const float inv = 1.0f / den;
     for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x) {
         float acc = 0.f;
-        for (int u = 0; u < nu; ++u) {
+        for (int u = 0; u < units; ++u) {
             const float *r = base + u * recsz;
             acc += __expf(r[(size_t)Tq * Dh + n] - mt) * r[(size_t)n * Dh + dim];
         }
@@ -231,16 +280,28 @@ __global__ void attn_merge_kernel(const float *__restrict__ apart, const int32_t
     }
 }
 
+// upper bound of workgroups per (b, h) that the partial buffer is sized for
 int attn_units(const hydra_ctx *c, int B) {
-    const int QG = ceil_div(ceil_div(c->tree.T, 32), 2);
-    int u = 1024 / (B * c->m.n_heads * QG);
+    int u = 512 / (B * c->m.n_heads);
     if (u < 1) u = 1;
-    if (u > 32) u = 32;
+    if (u > 16) u = 16;
     return u;
 }
 
 int launch_attention_f32(hydra_ctx *c, hipStream_t s, int B, int layer, const float *q, const int32_t *seq_len,
                          const hydra_kv *kv, float *out, int32_t *flags);
+
+static size_t attn_lds_bytes(int Dh) { return ((size_t)ATTN_WAVES * 64 + (size_t)ATTN_WAVES * (Dh / 32) * 16 * 64) * 4; }
+
+int attn_max_dynamic_lds(hydra_ctx *c) {
+    (void)c;
+    hipError_t e = hipSuccess;
+#define ATTR(DHv, Pv) if (e == hipSuccess) e = hipFuncSetAttribute((const void *)attn_bf16_kernel<DHv, Pv>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
+    ATTR(128, true); ATTR(128, false); ATTR(64, true); ATTR(64, false);
+#undef ATTR
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(attn_bf16_kernel)");
+    return HYDRA_OK;
+}
 
 // x_out != NULL: result as the next GEMM's input; plain_out != NULL: fp32 [B,T,H,Dh].
 int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *qbuf, const int32_t *seq_len,
@@ -251,32 +312,34 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     }
     const int T = c->tree.T, H = c->m.n_heads, Dh = c->m.head_dim;
     const int QTtot = ceil_div(T, 32);
-    const int QT = QTtot >= 2 ? 2 : 1;
-    const int QG = ceil_div(QTtot, QT);
-    // units: enough waves to fill the chip, but not more than one per two key tiles
-    int units = units_max;
-    if (kv->seq_len_hint > 0) {
-        const int tiles = ceil_div(kv->seq_len_hint + T, 32);
-        const int want = ceil_div(tiles, 2);
-        if (want < units) units = want;
-    }
-    if (units < 1) units = 1;
-    dim3 grid(ceil_div(units, 4), H, B * QG), block(256);
+    const int QW = QTtot >= 3 ? 4 : QTtot;                 // 1, 2 or 4 query waves
+    const int KWV = ATTN_WAVES / QW;
+    // workgroups per (b, h): one unless the context is long; each key-split wave should see >= 4 tiles
+    int wgs = 1;
+    const int len = kv->seq_len_hint > 0 ? kv->seq_len_hint : c->m.max_pos;
+    const int tiles = ceil_div(len + T, 32);
+    wgs = ceil_div(tiles, KWV * 4);
+    if (wgs > units_max) wgs = units_max;
+    if (wgs < 1) wgs = 1;
+    dim3 grid(wgs, H, B), block(ATTN_WAVES * 64);
     const float scale = 1.0f / sqrtf((float)Dh);
-#define ATTN_CASE(QTv, DHv)                                                                                          \
-    hipLaunchKernelGGL((attn_bf16_kernel<QTv, DHv>), grid, block, 0, s, (const u32x4_t *)qbuf,                        \
+    const size_t lds = attn_lds_bytes(Dh);
+    void *out = x_out ? x_out : (void *)plain_out;
+    const bool packed = x_out != nullptr;
+#define ATTN_CASE(DHv, Pv)                                                                                           \
+    hipLaunchKernelGGL((attn_bf16_kernel<DHv, Pv>), grid, block, lds, s, (const u32x4_t *)qbuf,                       \
                        (const bf16_t *)kv->k_pages, (const bf16_t *)kv->v_pages, kv->page_table, kv->max_pages,      \
-                       kv->n_pages, layer, seq_len, tree_dev(c), H, units, QG, scale, apart, flags)
-    if (QT == 1 && Dh == 128) ATTN_CASE(1, 128);
-    else if (QT == 2 && Dh == 128) ATTN_CASE(2, 128);
-    else if (QT == 1 && Dh == 64) ATTN_CASE(1, 64);
-    else ATTN_CASE(2, 64);
+                       kv->n_pages, layer, seq_len, tree_dev(c), H, QW, scale, apart, out, flags)
+    if (Dh == 128) { if (packed) ATTN_CASE(128, true); else ATTN_CASE(128, false); }
+    else           { if (packed) ATTN_CASE(64, true); else ATTN_CASE(64, false); }
 #undef ATTN_CASE
     HYDRA_LAUNCH_CHECK("attn_bf16_kernel");
-    dim3 mgrid(T, H, B), mblock(Dh);
-    if (x_out) hipLaunchKernelGGL(attn_merge_kernel<true>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, units, kv->max_pages, x_out);
-    else       hipLaunchKernelGGL(attn_merge_kernel<false>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, units, kv->max_pages, (void *)plain_out);
-    HYDRA_LAUNCH_CHECK("attn_merge_kernel");
+    if (wgs > 1) {
+        dim3 mgrid(T, H, B), mblock(Dh);
+        if (packed) hipLaunchKernelGGL(attn_merge_kernel<true>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, wgs, kv->max_pages, out);
+        else        hipLaunchKernelGGL(attn_merge_kernel<false>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, wgs, kv->max_pages, out);
+        HYDRA_LAUNCH_CHECK("attn_merge_kernel");
+    }
     return HYDRA_OK;
 }
 

@@ -1,179 +1,278 @@
-// bf16 storage family: the weight-streaming GEMM on MFMA, and the kernels that
-// bring plain row-major weights into its operand order.
-//
-//   part[split][m][n] = sum_{k in split} X[m][k] * W[n][k]      (fp32)
-//
-// The matrix W (N x K, bf16) is the only large operand: at M <= 128 rows every
-// weight byte is used once, so the kernel is a stream over W that must keep
-// enough bytes in flight to cover HBM latency.  Layout: W is stored as 32 x 16
-// (n x k) tiles of 1 KiB in the register order of the 32x32x16 MFMA "B"
-// operand (lane = (k%16)/8*32 + n%32 holds 8 consecutive k), tiles of one
-// 32-row band contiguous along k.  A wave owns NT bands; its load of one tile
-// is one fully coalesced 16-byte-per-lane instruction and goes straight to
-// registers.  X (M x K, bf16, same tile order, "A" operand) is small and shared
-// by all waves of a workgroup: it is staged through LDS in chunks.
-// Split-K partial sums are left to the consumer kernel (fixed order => the
-// result does not depend on scheduling).
-#include "device_common.h"
+// bf16 storage family: launch plans and epilogues of the weight-streaming GEMM
+// (kernel in gemm_bf16.h), and the kernels that bring plain row-major weights
+// into its tile order.
+#include "gemm_bf16.h"
 #include "internal.h"
 
 namespace hydra {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+// rows of a lane's accumulator registers
+__device__ __forceinline__ int acc_row(int mb, int v, int lane) { return mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
-enum { GEMM_U = 4 };   // k-steps per register block (prefetch distance)
-
-template <int MB, int NT, int CHUNK>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t *__restrict__ Xp, const u32x4_t *__restrict__ Wp,
-                                                         float *__restrict__ part, int M, int Npad, int NTiles, int KT,
-                                                         int kt_per_split, size_t split_stride) {
-    __shared__ u32x4_t xs[MB * CHUNK * 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int tile0 = (blockIdx.x * nwaves + wave) * NT;
-    const int kt_begin = blockIdx.y * kt_per_split;
-    const int kt_end = min(KT, kt_begin + kt_per_split);
-    const int mb0 = blockIdx.z * MB;
-
-    const u32x4_t *wrow[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int tile = min(tile0 + t, NTiles - 1);            // clamped: surplus waves stream a valid band and discard it
-        wrow[t] = Wp + (size_t)tile * KT * 64 + lane;
+// rstd[r] for the 32*MB rows of this row group, from the per-band sums of squares
+// ss[band][Mpad] left by the residual epilogue:  1 / sqrt(sum_band ss / d + eps).
+// Every kw == 0 wave fills the whole scratch itself, so no barrier is needed.
+template <int MB>
+__device__ __forceinline__ void rstd_to_lds(float *lds, const float *ss, int nb, int Mpad, int row0, int d, float eps,
+                                            int lane) {
+    for (int r = lane; r < 32 * MB; r += 64) {
+        const float *p = ss + row0 + r;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int b = 0;
+        for (; b + 4 <= nb; b += 4) {
+            s0 += p[(size_t)b * Mpad]; s1 += p[(size_t)(b + 1) * Mpad];
+            s2 += p[(size_t)(b + 2) * Mpad]; s3 += p[(size_t)(b + 3) * Mpad];
+        }
+        for (; b < nb; ++b) s0 += p[(size_t)b * Mpad];
+        lds[r] = 1.0f / sqrtf(((s0 + s1) + (s2 + s3)) / (float)d + eps);
     }
-    f32x16_t acc[MB][NT];
-#pragma unroll
-    for (int a = 0; a < MB; ++a)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][t][v] = 0.f;
+}
 
-    u32x4_t wa[GEMM_U][NT], wb[GEMM_U][NT];
-    auto load_w = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
+// ---- epilogues --------------------------------------------------------------
+// out[split][row][col] = acc
+struct EpiPlain {
+    float *out; int ld; size_t split_stride;
+    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    template <int MB, int NT> __device__ void operator()(GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        float *dst = out + (size_t)t.split * split_stride;
 #pragma unroll
-        for (int u = 0; u < GEMM_U; ++u)
+        for (int i = 0; i < NT; ++i) {
+            if (t.tile0 + i >= g.NTiles) continue;
+            const int col = (t.tile0 + i) * 32 + (t.lane & 31);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[u][t] = wrow[t][(size_t)(k0 + u) * 64];
-    };
-    auto refill = [&](int k0) {     // stage X k-steps [k0, k0+CHUNK) of the MB row blocks into LDS
-        const int cn = min(CHUNK, kt_end - k0);
-        __syncthreads();
+            for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int a = 0; a < MB; ++a)
-            for (int i = threadIdx.x; i < cn * 64; i += blockDim.x)
-                xs[a * CHUNK * 64 + i] = Xp[((size_t)(mb0 + a) * KT + k0) * 64 + i];
-        __syncthreads();
-    };
-    auto compute = [&](u32x4_t (&w)[GEMM_U][NT], int kl) {     // kl = k-step offset inside the LDS chunk
-#pragma unroll
-        for (int u = 0; u < GEMM_U; ++u)
-#pragma unroll
-            for (int a = 0; a < MB; ++a) {
-                const bf16x8_t xa = __builtin_bit_cast(bf16x8_t, xs[(a * CHUNK + kl + u) * 64 + lane]);
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, __builtin_bit_cast(bf16x8_t, w[u][t]), acc[a][t], 0, 0, 0);
-            }
-    };
-
-    load_w(wa, kt_begin);
-    for (int k0 = kt_begin; k0 < kt_end; k0 += 2 * GEMM_U) {
-        if ((k0 - kt_begin) % CHUNK == 0) refill(k0);
-        const bool has_b = k0 + GEMM_U < kt_end;
-        if (has_b) load_w(wb, k0 + GEMM_U);
-        compute(wa, (k0 - kt_begin) % CHUNK);
-        if (has_b) {
-            if ((k0 + GEMM_U - kt_begin) % CHUNK == 0) refill(k0 + GEMM_U);
-            if (k0 + 2 * GEMM_U < kt_end) load_w(wa, k0 + 2 * GEMM_U);
-            compute(wb, (k0 + GEMM_U - kt_begin) % CHUNK);
+                for (int v = 0; v < 16; ++v) {
+                    const int row = acc_row(t.mb0 + a, v, t.lane);
+                    if (row < g.M) dst[(size_t)row * ld + col] = t.acc[a][i][v];
+                }
         }
     }
+};
 
-    float *dst = part + (size_t)blockIdx.y * split_stride;
+// Residual branch end: x += acc.  Also leaves what the next RMSNorm'd GEMM needs:
+// xg = bf16(x * gain) in GEMM input order (the 1/rms factor commutes with the
+// contraction and is applied by the consumer) and ss[band][row] = sum over the
+// band's 32 columns of x^2.
+struct EpiResid {
+    float *x; int d; const float *gain; bf16_t *xg; float *ss; int Mpad;
+    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    template <int MB, int NT> __device__ void operator()(GemmTile<MB, NT> &t, const GemmGeom &g) const {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        if (tile0 + t >= NTiles) continue;
-        const int col = (tile0 + t) * 32 + (lane & 31);
+        for (int i = 0; i < NT; ++i) {
+            if (t.tile0 + i >= g.NTiles) continue;
+            const int band = t.tile0 + i;
+            const int col = band * 32 + (t.lane & 31);
+            const float gn = gain[col];
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = acc_row(t.mb0 + a, v, t.lane);
+                    float sq = 0.f;
+                    if (row < g.M) {
+                        const float xn = x[(size_t)row * d + col] + t.acc[a][i][v];
+                        x[(size_t)row * d + col] = xn;
+                        xg[x_index<true>(row, col, d)] = f2bf(xn * gn);
+                        sq = xn * xn;
+                    }
+#pragma unroll
+                    for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);      // over the 32 columns of the band
+                    if ((t.lane & 31) == 0 && row < g.M) ss[(size_t)band * Mpad + row] = sq;
+                }
+        }
+    }
+};
+
+// SwiGLU: bands (2j, 2j+1) hold gate and up of features 32j..32j+31.
+// act = SiLU(r * gate) * (r * up) with r = rstd[row] of the RMSNorm that feeds this GEMM.
+struct EpiSilu {
+    const float *ss; int nb; int Mpad; int dmodel; float eps; bf16_t *act; int F;
+    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &t, const GemmGeom &, int wave) const {
+        (void)wave;
+        rstd_to_lds<MB>(t.lds, ss, nb, Mpad, t.mb0 * 32, dmodel, eps, t.lane);
+    }
+    template <int MB, int NT> __device__ void operator()(GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        static_assert(NT == 2, "gate/up pairs need two bands per wave");
+        const int f = (t.tile0 >> 1) * 32 + (t.lane & 31);
 #pragma unroll
         for (int a = 0; a < MB; ++a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = (mb0 + a) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (row < M) dst[(size_t)row * Npad + col] = acc[a][t][v];
+                const int row = acc_row(t.mb0 + a, v, t.lane);
+                if (row >= g.M) continue;
+                const float r = t.lds[row - t.mb0 * 32];
+                act[x_index<true>(row, f, F)] = f2bf(silu_f(r * t.acc[a][0][v]) * (r * t.acc[a][1][v]));
             }
     }
-}
+};
 
+// Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
+struct EpiBiasSilu {
+    const float *bias; float *z; int d; int residual; bf16_t *xg;
+    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    template <int MB, int NT> __device__ void operator()(GemmTile<MB, NT> &t, const GemmGeom &g) const {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            if (t.tile0 + i >= g.NTiles) continue;
+            const int col = (t.tile0 + i) * 32 + (t.lane & 31);
+            const float bv = bias[col];
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = acc_row(t.mb0 + a, v, t.lane);
+                    if (row >= g.M) continue;
+                    float y = silu_f(t.acc[a][i][v] + bv);
+                    if (residual) y += z[(size_t)row * d + col];
+                    z[(size_t)row * d + col] = y;
+                    xg[x_index<true>(row, col, d)] = f2bf(y);
+                }
+        }
+    }
+};
+
+// ---- launch plans ---------------------------------------------------------------
 int gemm_npad(const hydra_ctx *c, int N) { return c->bf16 ? ceil_div(N, 32) * 32 : N; }
 
-GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K) {
+// A workgroup is NW x KW waves of up to 8; the grid should cover every CU (256) at
+// least once, and a wave should own at least 8 k-steps.  `pairs`: NT must be 2.
+GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, bool pairs, bool allow_split) {
     GemmPlan p;
-    if (!c->bf16) { p.mb = 1; p.nt = 1; p.waves = 4; p.splits = 1; p.kt_per_split = K; return p; }
+    p.splits = 1;
+    if (!c->bf16) { p.mb = 1; p.nt = 1; p.nw = 1; p.kw = 1; p.kpw = K; return p; }
     const int mblocks = ceil_div(M, 32);
     p.mb = mblocks >= 4 ? 4 : (mblocks >= 2 ? 2 : 1);
-    const int ntiles = ceil_div(N, 32), KT = K / 16;
-    p.waves = 4;
-    p.nt = (ntiles >= 512) ? 2 : 1;
-    const int wg_n = ceil_div(ntiles, p.waves * p.nt);
+    const int bands = ceil_div(N, 32), KT = K / 16;
+    p.nt = (pairs || bands >= 512) ? 2 : 1;
+    const int groups = ceil_div(bands, p.nt);
+    p.nw = 1;
+    p.kw = 4;
+    while (p.kw > 1 && KT / p.kw < 8) p.kw >>= 1;
+    // many row groups (large batch): workgroups are plentiful, share X between N-waves instead of splitting K
     const int mgroups = ceil_div(mblocks, p.mb);
-    int S = 1;
-    if (M <= 128) {
-        S = (640 + wg_n * mgroups - 1) / (wg_n * mgroups);
-        const int smax = KT / 16 > 0 ? KT / 16 : 1;
-        if (S > smax) S = smax;
-        if (S < 1) S = 1;
+    if (mgroups >= 2) { p.nw = 2; p.kw = 2; }
+    int wgs = ceil_div(groups, p.nw) * mgroups;
+    if (wgs < 256 && p.kw == 4 && KT / 8 >= 8) p.kw = 8;      // few workgroups: more waves (bytes in flight) per CU
+    if (allow_split && wgs < 192) {
+        int s = (256 + wgs - 1) / wgs;
+        while (s > 1 && KT / (p.kw * s) < 8) --s;
+        p.splits = s;
     }
-    int kps = ceil_div(ceil_div(KT, S), 2 * GEMM_U) * 2 * GEMM_U;
-    if (kps > KT) kps = KT;
-    p.kt_per_split = kps;
-    p.splits = ceil_div(KT, kps);
+    p.kpw = ceil_div(KT, p.kw * p.splits);
     return p;
 }
 
 int launch_gemm_f32(hydra_ctx *c, hipStream_t s, const float *X, const float *W, float *part, int M, int N, int K);
 
-int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float *part, int M, int N, int K,
-                GemmPlan *plan_out) {
-    GemmPlan p = plan_gemm(c, M, N, K);
-    if (plan_out) *plan_out = p;
+template <class Epi>
+static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
+                       const GemmPlan &p, const Epi &epi) {
+    GemmGeom g;
+    g.X = (const u32x4_t *)X; g.W = (const u32x4_t *)W;
+    g.M = M; g.NTiles = ceil_div(N, 32); g.KT = K / 16; g.kpw = p.kpw; g.NW = p.nw; g.KW = p.kw;
+    const int groups = ceil_div(g.NTiles, p.nt);
+    dim3 grid(ceil_div(groups, p.nw), p.splits, ceil_div(ceil_div(M, 32), p.mb)), block(p.nw * p.kw * 64);
+    const size_t lds = ((size_t)GEMM_LDS_SCRATCH + (size_t)(p.kw / 2) * p.nw * p.mb * p.nt * 16 * 64) * 4;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->profiling) {
-        if (c->ev_used + 2 > c->ev.size()) {
+        if (c->ev_used + 2 > c->ev.size())
             for (int i = 0; i < 2; ++i) { hipEvent_t e; HYDRA_HIP(hipEventCreate(&e)); c->ev.push_back(e); }
-        }
         e0 = c->ev[c->ev_used++]; e1 = c->ev[c->ev_used++];
         HYDRA_HIP(hipEventRecord(e0, s));
     }
-    int rc = HYDRA_OK;
-    if (!c->bf16) {
-        rc = launch_gemm_f32(c, s, (const float *)X, (const float *)W, part, M, N, K);
-    } else {
-        const int ntiles = ceil_div(N, 32), KT = K / 16, npad = ntiles * 32;
-        const int mblocks = ceil_div(M, 32);
-        dim3 grid(ceil_div(ntiles, p.waves * p.nt), p.splits, ceil_div(mblocks, p.mb)), block(p.waves * 64);
-        const size_t split_stride = (size_t)ceil_div(M, 32) * 32 * npad;
-        const u32x4_t *Xp = (const u32x4_t *)X, *Wp = (const u32x4_t *)W;
-#define GEMM_CASE(MBv, NTv, CHv)                                                                                     \
-    hipLaunchKernelGGL((gemm_bf16_kernel<MBv, NTv, CHv>), grid, block, 0, s, Xp, Wp, part, M, npad, ntiles, KT,      \
-                       p.kt_per_split, split_stride)
-        if (p.mb == 1 && p.nt == 1) GEMM_CASE(1, 1, 32);
-        else if (p.mb == 1 && p.nt == 2) GEMM_CASE(1, 2, 32);
-        else if (p.mb == 2 && p.nt == 1) GEMM_CASE(2, 1, 32);
-        else if (p.mb == 2 && p.nt == 2) GEMM_CASE(2, 2, 32);
-        else if (p.mb == 4 && p.nt == 1) GEMM_CASE(4, 1, 16);
-        else GEMM_CASE(4, 2, 16);
+#define GEMM_CASE(MBv, NTv)                                                                                          \
+    hipLaunchKernelGGL((gemm_bf16_kernel<MBv, NTv, 512, Epi>), grid, block, lds, s, g, epi)
+    if (p.mb == 1 && p.nt == 1) GEMM_CASE(1, 1);
+    else if (p.mb == 1 && p.nt == 2) GEMM_CASE(1, 2);
+    else if (p.mb == 2 && p.nt == 1) GEMM_CASE(2, 1);
+    else if (p.mb == 2 && p.nt == 2) GEMM_CASE(2, 2);
+    else if (p.mb == 4 && p.nt == 1) GEMM_CASE(4, 1);
+    else GEMM_CASE(4, 2);
 #undef GEMM_CASE
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) rc = hip_fail(e, "gemm_bf16_kernel");
-    }
+    HYDRA_LAUNCH_CHECK("gemm_bf16_kernel");
     if (c->profiling) {
         HYDRA_HIP(hipEventRecord(e1, s));
-        c->prof_bytes += (double)N * K * c->esz;
+        c->prof_bytes += (double)N * K * 2;
         c->prof_launches += 1;
     }
-    return rc;
+    return HYDRA_OK;
+}
+
+// SiLU epilogue needs NT == 2: instantiate only those
+static int launch_bf16_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
+                            const GemmPlan &p, const EpiSilu &epi) {
+    GemmGeom g;
+    g.X = (const u32x4_t *)X; g.W = (const u32x4_t *)W;
+    g.M = M; g.NTiles = ceil_div(N, 32); g.KT = K / 16; g.kpw = p.kpw; g.NW = p.nw; g.KW = p.kw;
+    const int groups = ceil_div(g.NTiles, 2);
+    dim3 grid(ceil_div(groups, p.nw), 1, ceil_div(ceil_div(M, 32), p.mb)), block(p.nw * p.kw * 64);
+    const size_t lds = ((size_t)GEMM_LDS_SCRATCH + (size_t)(p.kw / 2) * p.nw * p.mb * 2 * 16 * 64) * 4;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->profiling) {
+        if (c->ev_used + 2 > c->ev.size())
+            for (int i = 0; i < 2; ++i) { hipEvent_t e; HYDRA_HIP(hipEventCreate(&e)); c->ev.push_back(e); }
+        e0 = c->ev[c->ev_used++]; e1 = c->ev[c->ev_used++];
+        HYDRA_HIP(hipEventRecord(e0, s));
+    }
+    if (p.mb == 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 2, 512, EpiSilu>), grid, block, lds, s, g, epi);
+    else if (p.mb == 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 2, 512, EpiSilu>), grid, block, lds, s, g, epi);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<4, 2, 512, EpiSilu>), grid, block, lds, s, g, epi);
+    HYDRA_LAUNCH_CHECK("gemm_bf16_kernel<silu>");
+    if (c->profiling) {
+        HYDRA_HIP(hipEventRecord(e1, s));
+        c->prof_bytes += (double)N * K * 2;
+        c->prof_launches += 1;
+    }
+    return HYDRA_OK;
+}
+
+// part[split][m][n]  (fp32 family: one split, plain row-major operands)
+int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float *part, int M, int N, int K,
+                GemmPlan *plan_out) {
+    GemmPlan p = plan_gemm(c, M, N, K, false, true);
+    if (plan_out) *plan_out = p;
+    if (!c->bf16) return launch_gemm_f32(c, s, (const float *)X, (const float *)W, part, M, N, K);
+    const int npad = gemm_npad(c, N);
+    EpiPlain epi{part, npad, (size_t)ceil_div(M, 32) * 32 * npad};
+    return launch_bf16(c, s, X, W, M, N, K, p, epi);
+}
+
+int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *x,
+                      const float *gain, void *xg, float *ss, int Mpad) {
+    GemmPlan p = plan_gemm(c, M, N, K, false, false);
+    EpiResid epi{x, N, gain, (bf16_t *)xg, ss, Mpad};
+    return launch_bf16(c, s, X, W, M, N, K, p, epi);
+}
+
+int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
+                     int nb, int Mpad, void *act) {
+    GemmPlan p = plan_gemm(c, M, 2 * F, K, true, false);
+    EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (bf16_t *)act, F};
+    return launch_bf16_silu(c, s, X, W, M, 2 * F, K, p, epi);
+}
+
+int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
+                          const float *bias, float *z, bool residual, void *xg) {
+    GemmPlan p = plan_gemm(c, M, N, K, false, false);
+    EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (bf16_t *)xg};
+    return launch_bf16(c, s, X, W, M, N, K, p, epi);
+}
+
+int gemm_max_dynamic_lds(hydra_ctx *c) {
+    (void)c;
+    // opt in to the full LDS for every instantiation (a no-op for those that need less)
+    hipError_t e = hipSuccess;
+#define ATTR(MBv, NTv, E)                                                                                            \
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<MBv, NTv, 512, E>,                    \
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
+    ATTR(1, 1, EpiPlain); ATTR(1, 2, EpiPlain); ATTR(2, 1, EpiPlain); ATTR(2, 2, EpiPlain); ATTR(4, 1, EpiPlain); ATTR(4, 2, EpiPlain);
+    ATTR(1, 1, EpiResid); ATTR(1, 2, EpiResid); ATTR(2, 1, EpiResid); ATTR(2, 2, EpiResid); ATTR(4, 1, EpiResid); ATTR(4, 2, EpiResid);
+    ATTR(1, 1, EpiBiasSilu); ATTR(1, 2, EpiBiasSilu); ATTR(2, 1, EpiBiasSilu); ATTR(2, 2, EpiBiasSilu); ATTR(4, 1, EpiBiasSilu); ATTR(4, 2, EpiBiasSilu);
+    ATTR(1, 2, EpiSilu); ATTR(2, 2, EpiSilu); ATTR(4, 2, EpiSilu);
+#undef ATTR
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(gemm_bf16_kernel)");
+    return HYDRA_OK;
 }
 
 // ---------------------------------------------------------------------------

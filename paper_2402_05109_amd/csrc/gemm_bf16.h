@@ -1,0 +1,157 @@
+// The weight-streaming bf16 GEMM of the bf16 storage family (device code).
+//
+//   C[m][n] = sum_k X[m][k] * W[n][k]       fp32 accumulation
+//
+// At M <= 128 rows every weight byte is used once, so the kernel is a stream
+// over W that has to keep HBM busy.  W (N x K, bf16) is stored as 32 x 16
+// (n x k) tiles of 1 KiB in the register order of the 32x32x16 MFMA "B" operand
+// (lane = (k%16)/8*32 + n%32 holds 8 consecutive k); the tiles of one 32-row
+// band are contiguous along k.  X uses the same tile order ("A" operand).
+//
+// Work split.  A wave owns NT bands and a contiguous run of k-steps; it loads
+// its W tiles (and the matching X tiles, which hit in L1/L2) straight into
+// registers with fully coalesced 16-byte-per-lane loads, U k-steps ahead of
+// the MFMAs, and never synchronises with other waves while streaming.  A
+// workgroup is NW x KW waves: KW waves share a band group and split K; their
+// accumulators are summed through LDS in a fixed binary tree, so the order of
+// every sum is fixed and results do not depend on scheduling.  grid.y = S > 1
+// splits K over workgroups as well; then each split hands its own partial tile
+// to the epilogue (only epilogues that write per-split outputs accept S > 1).
+//
+// The epilogue is a functor invoked by the kw == 0 waves with the finished
+// accumulators in the MFMA layout
+//   acc[a][t][v]  ->  row = 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,   col = 32*(tile0+t) + lane%32.
+// `Epilogue::prologue` runs in every wave before streaming starts, after the
+// first loads have been issued (used to prepare per-row scales in LDS).
+#pragma once
+
+#include "device_common.h"
+
+namespace hydra {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+struct GemmGeom {
+    const u32x4_t *X, *W;
+    int M;          // valid rows
+    int NTiles;     // 32-column bands of W (N padded up)
+    int KT;         // k-steps of 16 in K
+    int kpw;        // k-steps per wave
+    int NW, KW;     // waves per workgroup along N and K (KW a power of two)
+};
+
+enum { GEMM_LDS_SCRATCH = 256 };   // floats reserved in front of the reduction buffer
+
+// prefetch distance in k-steps: two register sets of U*(NT+MB) KiB per wave
+template <int MB, int NT> struct GemmU { enum { value = (MB + NT >= 6) ? 2 : 4 }; };
+
+template <int MB, int NT>
+struct GemmTile {
+    f32x16_t acc[MB][NT];
+    int tile0;      // first band of this wave
+    int mb0;        // first 32-row block
+    int lane;
+    int split;      // blockIdx.y
+    float *lds;     // GEMM_LDS_SCRATCH floats of per-workgroup scratch
+};
+
+template <int MB, int NT, int MAXT, class Epilogue>
+__global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
+    constexpr int GEMM_U = GemmU<MB, NT>::value;
+    extern __shared__ float red[];                 // [scratch] + [KW/2][NW][MB*NT*16][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nw = wave % g.NW, kw = wave / g.NW;
+    const int group = blockIdx.x * g.NW + nw;       // band group of this wave
+    GemmTile<MB, NT> t;
+    t.tile0 = group * NT;
+    t.mb0 = blockIdx.z * MB;
+    t.lane = lane;
+    t.split = blockIdx.y;
+    t.lds = red;
+    float *redbuf = red + GEMM_LDS_SCRATCH;
+    const int k_begin = min(g.KT, (int)(blockIdx.y * g.KW + kw) * g.kpw);
+    const int k_end = min(g.KT, k_begin + g.kpw);
+
+    const u32x4_t *wrow[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) wrow[i] = g.W + (size_t)min(t.tile0 + i, g.NTiles - 1) * g.KT * 64 + lane;
+    const u32x4_t *xrow[MB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a) xrow[a] = g.X + (size_t)(t.mb0 + a) * g.KT * 64 + lane;
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t.acc[a][i][v] = 0.f;
+
+    u32x4_t wa[GEMM_U][NT], xa[GEMM_U][MB], wb[GEMM_U][NT], xb[GEMM_U][MB];
+    auto load = [&](u32x4_t (&w)[GEMM_U][NT], u32x4_t (&x)[GEMM_U][MB], int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int k = min(k0 + u, g.KT - 1);         // clamped: a ragged tail re-reads a valid tile and skips its MFMA
+#pragma unroll
+            for (int i = 0; i < NT; ++i) w[u][i] = wrow[i][(size_t)k * 64];
+#pragma unroll
+            for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
+        }
+    };
+    auto compute = [&](u32x4_t (&w)[GEMM_U][NT], u32x4_t (&x)[GEMM_U][MB], int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            if (k0 + u < k_end) {
+#pragma unroll
+                for (int a = 0; a < MB; ++a)
+#pragma unroll
+                    for (int i = 0; i < NT; ++i)
+                        t.acc[a][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, x[u][a]),
+                                                                            __builtin_bit_cast(bf16x8_t, w[u][i]),
+                                                                            t.acc[a][i], 0, 0, 0);
+            }
+        }
+    };
+    if (k_begin < k_end) load(wa, xa, k_begin);
+    epi.prologue(t, g, wave);                          // overlaps with the first loads
+    if (k_begin < k_end) {
+        for (int k0 = k_begin; k0 < k_end; k0 += 2 * GEMM_U) {
+            if (k0 + GEMM_U < k_end) load(wb, xb, k0 + GEMM_U);
+            compute(wa, xa, k0);
+            if (k0 + GEMM_U < k_end) {
+                if (k0 + 2 * GEMM_U < k_end) load(wa, xa, k0 + 2 * GEMM_U);
+                compute(wb, xb, k0 + GEMM_U);
+            }
+        }
+    }
+
+    // ---- sum the KW accumulators of a band group through LDS, fixed binary tree
+    constexpr int ACC = MB * NT * 16;
+    for (int stride = g.KW >> 1; stride >= 1; stride >>= 1) {
+        if (kw >= stride && kw < 2 * stride) {
+            float *dst = redbuf + ((size_t)((kw - stride) * g.NW + nw) * ACC) * 64 + lane;
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((a * NT + i) * 16 + v) * 64] = t.acc[a][i][v];
+        }
+        __syncthreads();
+        if (kw < stride) {
+            const float *src = redbuf + ((size_t)(kw * g.NW + nw) * ACC) * 64 + lane;
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) t.acc[a][i][v] += src[((a * NT + i) * 16 + v) * 64];
+        }
+        __syncthreads();
+    }
+    if (kw != 0 || t.tile0 >= g.NTiles) return;
+    epi(t, g);
+}
+
+}  // namespace hydra

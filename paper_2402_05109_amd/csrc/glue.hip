@@ -23,6 +23,64 @@ __global__ void embed_kernel(const typename Elem<BF>::type *E, const int32_t *to
     for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)m * d + k] = Elem<BF>::ld(E, (size_t)tok * d + k);
 }
 
+// 1 / rms of row m from the per-band sums of squares (one wave's worth of threads adds the bands)
+__device__ __forceinline__ float row_rstd_block(const RowScale &rs, int m, float *sh) {
+    if (!rs.ss) return 1.0f;
+    float a = 0.f;
+    if (threadIdx.x < 64)
+        for (int b = threadIdx.x; b < rs.nb; b += 64) a += rs.ss[(size_t)b * rs.Mpad + m];
+    if (threadIdx.x < 64) {
+        a = wave_sum(a);
+        if (threadIdx.x == 0) sh[0] = 1.0f / sqrtf(a / (float)rs.d + rs.eps);
+    }
+    __syncthreads();
+    return sh[0];
+}
+
+// bf16 family: x = E[token]; xg = bf16(x * gain) as GEMM input; ss[band][row] = sum of x^2 over the band
+__global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const int32_t *tokens, float *x,
+                                                          const float *gain, bf16_t *xg, float *ss, int Mpad, int d,
+                                                          int V, int32_t *flags) {
+    const int m = blockIdx.x;
+    int tok = tokens[m];
+    if (tok < 0 || tok >= V) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
+        tok = 0;
+    }
+    for (int k = threadIdx.x; k < d; k += 256) {       // d is a multiple of 256 is not required: guarded below
+        const float v = bf2f(E[(size_t)tok * d + k]);
+        x[(size_t)m * d + k] = v;
+        xg[x_index<true>(m, k, d)] = f2bf(v * gain[k]);
+        float sq = v * v;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+        if ((threadIdx.x & 31) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
+    }
+}
+
+int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
+                      float *ss, int Mpad, int M, int32_t *flags) {
+    hipLaunchKernelGGL(embed_prep_kernel, dim3(M), dim3(256), 0, s, (const bf16_t *)(c->arena + c->off_embed), tokens, x,
+                       gain, (bf16_t *)xg, ss, Mpad, c->m.d, c->m.vocab, flags);
+    HYDRA_LAUNCH_CHECK("embed_prep_kernel");
+    return HYDRA_OK;
+}
+
+// hidden[m][k] = x[m][k] * rstd[m] * gain[k]   (final RMSNorm, fp32 output of tree_verify_forward)
+__global__ __launch_bounds__(256) void final_hidden_kernel(const float *x, const float *gain, RowScale rs, float *hidden,
+                                                            int d) {
+    __shared__ float sh[1];
+    const int m = blockIdx.x;
+    const float r = row_rstd_block(rs, m, sh);
+    for (int k = threadIdx.x; k < d; k += 256) hidden[(size_t)m * d + k] = x[(size_t)m * d + k] * r * gain[k];
+}
+
+int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float *gain, RowScale rs, float *hidden, int M) {
+    hipLaunchKernelGGL(final_hidden_kernel, dim3(M), dim3(256), 0, s, x, gain, rs, hidden, c->m.d);
+    HYDRA_LAUNCH_CHECK("final_hidden_kernel");
+    return HYDRA_OK;
+}
+
 int launch_embed(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, int M, int32_t *flags) {
     const void *E = c->arena + c->off_embed;
     if (c->bf16) hipLaunchKernelGGL(embed_kernel<true>, dim3(M), dim3(256), 0, s, (const bf16_t *)E, tokens, x, c->m.d, c->m.vocab, flags);
@@ -100,7 +158,7 @@ __device__ __forceinline__ size_t q_index(int b, int n, int h, int dim, int H, i
 }
 
 template <bool BF>
-__global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t split_stride, const TreeDev *tree,
+__global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t split_stride, RowScale rs, const TreeDev *tree,
                                    const float *rope, const int32_t *seq_len, const int32_t *page_table,
                                    int max_pages, int n_pages, int layer, typename Elem<BF>::type *kpages,
                                    typename Elem<BF>::type *vpages, typename Elem<BF>::type *qbuf, int d, int H,
@@ -116,14 +174,16 @@ __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t
         if (threadIdx.x == 0) atomicOr(flags, FLAG_CAPACITY);
         return;
     }
+    __shared__ float sh[1];
+    const float r = row_rstd_block(rs, m, sh);
     const int half = Dh >> 1;
     const int j = threadIdx.x;
     if (j >= half) return;
     const size_t row = (size_t)m * part_ld;
     const int c0 = h * Dh + j, c1 = c0 + half;
-    const float q0 = part_sum(part, S, split_stride, row + c0), q1 = part_sum(part, S, split_stride, row + c1);
-    const float k0 = part_sum(part, S, split_stride, row + d + c0), k1 = part_sum(part, S, split_stride, row + d + c1);
-    const float v0 = part_sum(part, S, split_stride, row + 2 * d + c0), v1 = part_sum(part, S, split_stride, row + 2 * d + c1);
+    const float q0 = r * part_sum(part, S, split_stride, row + c0), q1 = r * part_sum(part, S, split_stride, row + c1);
+    const float k0 = r * part_sum(part, S, split_stride, row + d + c0), k1 = r * part_sum(part, S, split_stride, row + d + c1);
+    const float v0 = r * part_sum(part, S, split_stride, row + 2 * d + c0), v1 = r * part_sum(part, S, split_stride, row + 2 * d + c1);
     const float cs = rope[((size_t)pos * half + j) * 2], sn = rope[((size_t)pos * half + j) * 2 + 1];
     Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
     Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
@@ -137,13 +197,14 @@ __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t
 }
 
 int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
-                       int B, int layer, const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags) {
+                       RowScale rs, int B, int layer, const int32_t *seq_len, const hydra_kv *kv, void *qbuf,
+                       int32_t *flags) {
     const int T = c->tree.T;
     dim3 grid(B * T, c->m.n_heads), block(64);
     if (c->bf16)
-        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, (bf16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, (bf16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     else
-        hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+        hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     HYDRA_LAUNCH_CHECK("rope_append_kernel");
     return HYDRA_OK;
 }
@@ -208,12 +269,14 @@ __device__ __forceinline__ void top2_merge(Top2 &a, const Top2 &b) {
     else a.v2 = fmaxf(a.v2, b.v1);
 }
 
-__global__ __launch_bounds__(256) void argmax_kernel(const float *part, int S, int part_ld, size_t split_stride, int V,
-                                                      int32_t *argmax, float *margin, float *logits) {
+__global__ __launch_bounds__(256) void argmax_kernel(const float *part, int S, int part_ld, size_t split_stride,
+                                                      RowScale rs, int V, int32_t *argmax, float *margin, float *logits) {
     const int m = blockIdx.x;
+    __shared__ float sh[1];
+    const float r = row_rstd_block(rs, m, sh);
     Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
     for (int v = threadIdx.x; v < V; v += 256) {
-        const float x = part_sum(part, S, split_stride, (size_t)m * part_ld + v);
+        const float x = r * part_sum(part, S, split_stride, (size_t)m * part_ld + v);
         if (logits) logits[(size_t)m * V + v] = x;
         top2_push(t, x, v);
     }
@@ -233,9 +296,9 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float *part, int S, i
     }
 }
 
-int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, int M,
-                  int32_t *argmax, float *margin, float *logits) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, part, S, part_ld, split_stride, c->m.vocab, argmax, margin, logits);
+int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, RowScale rs,
+                  int M, int32_t *argmax, float *margin, float *logits) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
     HYDRA_LAUNCH_CHECK("argmax_kernel");
     return HYDRA_OK;
 }

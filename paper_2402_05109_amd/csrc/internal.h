@@ -39,10 +39,10 @@ struct HeadOff  { size_t w1, b1, wout; size_t wl[8], bl[8]; };   // wl[j], j = 2
 
 struct GemmPlan {      // launch shape of one weight-streaming GEMM (bf16 family)
     int mb;            // 32-row blocks per workgroup (1, 2 or 4)
-    int nt;            // 32-column tiles per wave (1 or 2)
-    int waves;         // waves per workgroup
-    int splits;        // split-K factor S
-    int kt_per_split;  // k-steps (of 16) per split
+    int nt;            // 32-column bands per wave (1 or 2)
+    int nw, kw;        // waves per workgroup along N and along K
+    int splits;        // workgroups along K (each writes its own partial output)
+    int kpw;           // k-steps (of 16) per wave
 };
 
 }  // namespace hydra
@@ -92,11 +92,11 @@ inline int    ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---- workspace ------------------------------------------------------------
 struct WsLayout {
-    size_t flags, x, xa, xb, part, qbuf, apart, z, total;
+    size_t flags, x, xa, xb, part, qbuf, apart, z, ss, total;
     int attn_units;     // split-KV units per (row, head, query group)
 };
 WsLayout ws_layout(const hydra_ctx *c, int B);
-GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K);
+GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, bool pairs, bool allow_split);
 int      attn_units(const hydra_ctx *c, int B);
 
 // ---- launchers (each enqueues on `s` and returns a hydra_status) -----------
@@ -106,6 +106,20 @@ int      attn_units(const hydra_ctx *c, int B);
 int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float *part,
                 int M, int N, int K, GemmPlan *plan_out);
 int gemm_npad(const hydra_ctx *c, int N);   // row stride of `part` for N outputs
+// bf16 family, fused epilogues (see bf16_gemm.hip)
+int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *x,
+                      const float *gain, void *xg, float *ss, int Mpad);
+int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
+                     int nb, int Mpad, void *act);
+int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
+                          const float *bias, float *z, bool residual, void *xg);
+int gemm_max_dynamic_lds(hydra_ctx *c);
+int attn_max_dynamic_lds(hydra_ctx *c);
+// per-row 1/rms from the per-band sums of squares ss[band][Mpad] (bf16 family); ss == NULL: no scaling
+struct RowScale { const float *ss; int nb; int Mpad; int d; float eps; };
+int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
+                      float *ss, int Mpad, int M, int32_t *flags);
+int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float *gain, RowScale rs, float *hidden, int M);
 
 // packing (arena loads)
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K,
@@ -120,13 +134,14 @@ int launch_embed(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, i
 int launch_rmsnorm(hydra_ctx *c, hipStream_t s, float *x, const float *part, int S, int part_ld, size_t part_split_stride,
                    const float *gain, void *x_out, int M, float *hidden_out);
 int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
-                       int B, int layer, const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags);
+                       RowScale rs, int B, int layer, const int32_t *seq_len, const hydra_kv *kv, void *qbuf,
+                       int32_t *flags);
 int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *qbuf, const int32_t *seq_len,
                      const hydra_kv *kv, float *apart, int units, void *x_out, float *plain_out, int32_t *flags);
 int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                     void *x_out, int M);
 int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
-                  int M, int32_t *argmax, float *margin, float *logits);
+                  RowScale rs, int M, int32_t *argmax, float *margin, float *logits);
 int launch_q_import(hydra_ctx *c, hipStream_t s, int B, const float *q_plain, void *qbuf);
 int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_kv *kv, int first_slot, int n_slots,
                     float *plain, bool write_cache);
