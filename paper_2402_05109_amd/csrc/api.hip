@@ -118,7 +118,7 @@ WsLayout ws_layout(const hydra_ctx *c, int B) {
     // split-K partial sums: the largest S * Mpad * Npad over every GEMM this context can launch
     size_t part = 0;
     auto need = [&](size_t m, size_t n, size_t k) {
-        GemmPlan p = plan_gemm(c, (int)m, (int)n, (int)k, false, true);
+        GemmPlan p = plan_gemm(c, (int)m, (int)n, (int)k, GEMM_KIND_PLAIN);
         const size_t mp = align_up(m, 32), np = (size_t)gemm_npad(c, (int)n);
         part = std::max(part, (size_t)p.splits * mp * np * 4);
     };
@@ -268,9 +268,10 @@ int hydra_load_tensor(hydra_ctx *c, void *stream, int kind, int index, int sub, 
     if (head_kind && (index < 1 || index > c->h.n_draft_heads)) return fail(HYDRA_E_INVALID_ARG, "head index out of range (1-based)");
     if ((kind == HYDRA_W_HEAD_WL || kind == HYDRA_W_HEAD_BL) && (sub < 2 || sub > c->h.mlp_layers))
         return fail(HYDRA_E_INVALID_ARG, "MLP layer index out of range (2..mlp_layers)");
-    auto matrix = [&](size_t off, int N, int K, int f32_row_off, int f32_rows_total, int tile_off, int tile_stride) -> int {
+    auto matrix = [&](size_t off, int N, int K, int f32_row_off, int f32_rows_total, int tile_off, int tile_stride,
+                      int rows_per_band = 32, int col_off = 0) -> int {
         (void)f32_rows_total;
-        if (c->bf16) return launch_pack_matrix(c, s, src, A + off, N, K, tile_off, tile_stride, 0);
+        if (c->bf16) return launch_pack_matrix(c, s, src, A + off, N, K, tile_off, tile_stride, rows_per_band, col_off);
         return launch_copy_matrix(c, s, src, A + off, N, K, f32_row_off, K);
     };
     switch (kind) {
@@ -283,8 +284,8 @@ int hydra_load_tensor(hydra_ctx *c, void *stream, int kind, int index, int sub, 
         case HYDRA_W_WK:         return matrix(c->layer[index].wqkv, d, d, d, 3 * d, d / 32, 1);
         case HYDRA_W_WV:         return matrix(c->layer[index].wqkv, d, d, 2 * d, 3 * d, 2 * (d / 32), 1);
         case HYDRA_W_WO:         return matrix(c->layer[index].wo, d, d, 0, d, 0, 1);
-        case HYDRA_W_GATE:       return matrix(c->layer[index].wgu, F, d, 0, 2 * F, 0, 2);
-        case HYDRA_W_UP:         return matrix(c->layer[index].wgu, F, d, F, 2 * F, 1, 2);
+        case HYDRA_W_GATE:       return matrix(c->layer[index].wgu, F, d, 0, 2 * F, 0, 1, 16, 0);     // bf16: left half of every band
+        case HYDRA_W_UP:         return matrix(c->layer[index].wgu, F, d, F, 2 * F, 0, 1, 16, 16);    // bf16: right half
         case HYDRA_W_DOWN:       return matrix(c->layer[index].wdown, d, F, 0, d, 0, 1);
         case HYDRA_W_HEAD_W1:    return matrix(c->head[index].w1, d, head_in_width(c, index), 0, d, 0, 1);
         case HYDRA_W_HEAD_B1:    return launch_to_f32(c, s, src, (float *)(A + c->head[index].b1), d);
@@ -409,9 +410,9 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
             if ((rc = launch_gemm(c, s, xa, A + o.wqkv, part, M, 3 * d, d, &p))) return rc;
             if ((rc = launch_rope_append(c, s, part, p.splits, ld_qkv, mp * ld_qkv, rs, B, l, seq_len, kv, qbuf, flags))) return rc;
             if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xb, nullptr, flags))) return rc;
-            if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad, part))) return rc;
             if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, d / 32, Mpad, xb))) return rc;
-            if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad, part))) return rc;
         }
         if ((rc = launch_final_hidden(c, s, x, (const float *)(A + c->off_final_norm), rs, hidden, M))) return rc;
         if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;

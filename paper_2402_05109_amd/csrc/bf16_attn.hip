@@ -314,11 +314,11 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     const int QTtot = ceil_div(T, 32);
     const int QW = QTtot >= 3 ? 4 : QTtot;                 // 1, 2 or 4 query waves
     const int KWV = ATTN_WAVES / QW;
-    // workgroups per (b, h): one unless the context is long; each key-split wave should see >= 4 tiles
+    // workgroups per (b, h): one unless the context is long (a key-split wave takes up to 16 tiles)
     int wgs = 1;
     const int len = kv->seq_len_hint > 0 ? kv->seq_len_hint : c->m.max_pos;
     const int tiles = ceil_div(len + T, 32);
-    wgs = ceil_div(tiles, KWV * 4);
+    wgs = ceil_div(tiles, KWV * 16);
     if (wgs > units_max) wgs = units_max;
     if (wgs < 1) wgs = 1;
     dim3 grid(wgs, H, B), block(ATTN_WAVES * 64);

@@ -12,17 +12,19 @@
 // its W tiles (and the matching X tiles, which hit in L1/L2) straight into
 // registers with fully coalesced 16-byte-per-lane loads, U k-steps ahead of
 // the MFMAs, and never synchronises with other waves while streaming.  A
-// workgroup is NW x KW waves: KW waves share a band group and split K; their
-// accumulators are summed through LDS in a fixed binary tree, so the order of
-// every sum is fixed and results do not depend on scheduling.  grid.y = S > 1
-// splits K over workgroups as well; then each split hands its own partial tile
-// to the epilogue (only epilogues that write per-split outputs accept S > 1).
+// workgroup is NW x KW waves: KW waves share a band group and split K.  All of
+// them leave their accumulators in LDS; then wave kw adds the KW copies of the
+// 32x32 tiles j = kw, kw + KW, ... in wave order (a fixed order, so results do
+// not depend on scheduling) and runs the epilogue on those tiles, which spreads
+// the epilogue over the workgroup.  grid.y = S > 1 splits K over workgroups as
+// well; then each split hands its own partial tiles to the epilogue (only
+// epilogues that write per-split outputs accept S > 1).
 //
-// The epilogue is a functor invoked by the kw == 0 waves with the finished
-// accumulators in the MFMA layout
-//   acc[a][t][v]  ->  row = 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,   col = 32*(tile0+t) + lane%32.
-// `Epilogue::prologue` runs in every wave before streaming starts, after the
-// first loads have been issued (used to prepare per-row scales in LDS).
+// The epilogue is a functor with
+//   tile(acc, a, i, t, g): one finished 32x32 tile in the MFMA layout,
+//       acc[v] -> row = 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,  col = 32*(tile0+i) + lane%32;
+//   prologue(t, g, wave): runs in every wave before streaming starts, after the
+//       first loads have been issued (used to prepare per-row scales in LDS).
 #pragma once
 
 #include "device_common.h"
@@ -43,14 +45,13 @@ struct GemmGeom {
     int NW, KW;     // waves per workgroup along N and K (KW a power of two)
 };
 
-enum { GEMM_LDS_SCRATCH = 256 };   // floats reserved in front of the reduction buffer
+enum { GEMM_LDS_SCRATCH = 128 + 8 * 64 };   // floats reserved in front of the reduction buffer: row scales + per-wave partials
 
 // prefetch distance in k-steps: two register sets of U*(NT+MB) KiB per wave
-template <int MB, int NT> struct GemmU { enum { value = (MB + NT >= 6) ? 2 : 4 }; };
+template <int MB, int NT> struct GemmU { enum { value = (MB * NT >= 6) ? 4 : ((MB + NT >= 6) ? 2 : 4) }; };
 
 template <int MB, int NT>
 struct GemmTile {
-    f32x16_t acc[MB][NT];
     int tile0;      // first band of this wave
     int mb0;        // first 32-row block
     int lane;
@@ -58,10 +59,9 @@ struct GemmTile {
     float *lds;     // GEMM_LDS_SCRATCH floats of per-workgroup scratch
 };
 
-template <int MB, int NT, int MAXT, class Epilogue>
+template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
 __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
-    constexpr int GEMM_U = GemmU<MB, NT>::value;
-    extern __shared__ float red[];                 // [scratch] + [KW/2][NW][MB*NT*16][64]
+    extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nw = wave % g.NW, kw = wave / g.NW;
     const int group = blockIdx.x * g.NW + nw;       // band group of this wave
@@ -81,12 +81,13 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     const u32x4_t *xrow[MB];
 #pragma unroll
     for (int a = 0; a < MB; ++a) xrow[a] = g.X + (size_t)(t.mb0 + a) * g.KT * 64 + lane;
+    f32x16_t acc[MB][NT];
 #pragma unroll
     for (int a = 0; a < MB; ++a)
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) t.acc[a][i][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[a][i][v] = 0.f;
 
     u32x4_t wa[GEMM_U][NT], xa[GEMM_U][MB], wb[GEMM_U][NT], xb[GEMM_U][MB];
     auto load = [&](u32x4_t (&w)[GEMM_U][NT], u32x4_t (&x)[GEMM_U][MB], int k0) {
@@ -107,51 +108,70 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
                 for (int a = 0; a < MB; ++a)
 #pragma unroll
                     for (int i = 0; i < NT; ++i)
-                        t.acc[a][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, x[u][a]),
-                                                                            __builtin_bit_cast(bf16x8_t, w[u][i]),
-                                                                            t.acc[a][i], 0, 0, 0);
+                        acc[a][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, x[u][a]),
+                                                                          __builtin_bit_cast(bf16x8_t, w[u][i]),
+                                                                          acc[a][i], 0, 0, 0);
             }
         }
     };
-    if (k_begin < k_end) load(wa, xa, k_begin);
+    // k-blocks of U steps are visited in an order rotated by the workgroup index, so that the
+    // workgroups streaming different bands do not all ask the L2 for the same X lines at once
+    const int nblk = (k_end - k_begin + GEMM_U - 1) / GEMM_U;
+#ifndef GEMM_EXP_NO_ROTATE
+    const int rot = nblk > 0 ? (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk) : 0;
+#else
+    const int rot = 0;
+#endif
+    auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return k_begin + q * GEMM_U; };
+    if (nblk > 0) load(wa, xa, kof(0));
     epi.prologue(t, g, wave);                          // overlaps with the first loads
-    if (k_begin < k_end) {
-        for (int k0 = k_begin; k0 < k_end; k0 += 2 * GEMM_U) {
-            if (k0 + GEMM_U < k_end) load(wb, xb, k0 + GEMM_U);
-            compute(wa, xa, k0);
-            if (k0 + GEMM_U < k_end) {
-                if (k0 + 2 * GEMM_U < k_end) load(wa, xa, k0 + 2 * GEMM_U);
-                compute(wb, xb, k0 + GEMM_U);
-            }
+    for (int j = 0; j < nblk; j += 2) {
+        if (j + 1 < nblk) load(wb, xb, kof(j + 1));
+        compute(wa, xa, kof(j));
+        if (j + 1 < nblk) {
+            if (j + 2 < nblk) load(wa, xa, kof(j + 2));
+            compute(wb, xb, kof(j + 1));
         }
     }
 
-    // ---- sum the KW accumulators of a band group through LDS, fixed binary tree
-    constexpr int ACC = MB * NT * 16;
-    for (int stride = g.KW >> 1; stride >= 1; stride >>= 1) {
-        if (kw >= stride && kw < 2 * stride) {
-            float *dst = redbuf + ((size_t)((kw - stride) * g.NW + nw) * ACC) * 64 + lane;
+    // ---- finish: KW == 1 keeps everything in registers; otherwise meet in LDS and share the tiles out
+    const bool live = t.tile0 < g.NTiles;                         // surplus waves streamed a clamped band: discard
+    if (g.KW == 1) {
+        if (!live) return;
 #pragma unroll
-            for (int a = 0; a < MB; ++a)
+        for (int a = 0; a < MB; ++a)
 #pragma unroll
-                for (int i = 0; i < NT; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) dst[((a * NT + i) * 16 + v) * 64] = t.acc[a][i][v];
-        }
-        __syncthreads();
-        if (kw < stride) {
-            const float *src = redbuf + ((size_t)(kw * g.NW + nw) * ACC) * 64 + lane;
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int i = 0; i < NT; ++i)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) t.acc[a][i][v] += src[((a * NT + i) * 16 + v) * 64];
-        }
-        __syncthreads();
+            for (int i = 0; i < NT; ++i) epi.tile(acc[a][i], a, i, t, g);
+        return;
     }
-    if (kw != 0 || t.tile0 >= g.NTiles) return;
-    epi(t, g);
+    constexpr int TILES = MB * NT;
+    {
+        float *dst = redbuf + ((size_t)(kw * g.NW + nw) * TILES) * 16 * 64 + lane;
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[((a * NT + i) * 16 + v) * 64] = acc[a][i][v];
+    }
+    __syncthreads();
+    if (!live) return;
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const int j = a * NT + i;
+            if (j % g.KW != kw) continue;                          // wave-uniform
+            f32x16_t sum;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+            for (int w = 0; w < g.KW; ++w) {
+                const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + j) * 16 * 64 + lane;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum[v] += src[v * 64];
+            }
+            epi.tile(sum, a, i, t, g);
+        }
 }
 
 }  // namespace hydra

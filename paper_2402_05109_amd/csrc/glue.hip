@@ -249,7 +249,7 @@ int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int p
                     void *x_out, int M) {
     const int F = c->m.ffn;
     dim3 grid(ceil_div(F, 256), M), block(256);
-    if (c->bf16) hipLaunchKernelGGL(silu_mul_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, F, 32, (bf16_t *)x_out);
+    if (c->bf16) hipLaunchKernelGGL(silu_mul_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, F, 16, (bf16_t *)x_out);
     else         hipLaunchKernelGGL(silu_mul_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, F, F, (float *)x_out);
     HYDRA_LAUNCH_CHECK("silu_mul_kernel");
     return HYDRA_OK;

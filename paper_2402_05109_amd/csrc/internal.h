@@ -96,7 +96,8 @@ struct WsLayout {
     int attn_units;     // split-KV units per (row, head, query group)
 };
 WsLayout ws_layout(const hydra_ctx *c, int B);
-GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, bool pairs, bool allow_split);
+enum { GEMM_KIND_PLAIN = 0, GEMM_KIND_FUSED = 1, GEMM_KIND_PAIRS = 2 };   // plain output (may split K) / fused epilogue / gate-up pairs
+GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind);
 int      attn_units(const hydra_ctx *c, int B);
 
 // ---- launchers (each enqueues on `s` and returns a hydra_status) -----------
@@ -108,7 +109,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
 int gemm_npad(const hydra_ctx *c, int N);   // row stride of `part` for N outputs
 // bf16 family, fused epilogues (see bf16_gemm.hip)
 int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *x,
-                      const float *gain, void *xg, float *ss, int Mpad);
+                      const float *gain, void *xg, float *ss, int Mpad, float *part);
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act);
 int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
@@ -123,7 +124,7 @@ int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float
 
 // packing (arena loads)
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K,
-                       int tile_off, int tile_stride, int n_tiles_total_for_pad);
+                       int tile_off, int tile_stride, int rows_per_band, int col_off);
 int launch_copy_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, size_t rows, size_t cols,
                        size_t dst_row_off, size_t dst_ld);
 int launch_to_f32(hydra_ctx *c, hipStream_t s, const void *src, float *dst, int n);
