@@ -39,9 +39,11 @@
  *     is skipped and flagged (see hydra_read_flags), never accessed out of
  *     bounds.
  *   - dtype HYDRA_F32: weights, KV cache and GEMM inputs are fp32.
- *     dtype HYDRA_BF16: weights and KV cache are bf16, GEMM inputs are rounded
- *     to bf16, all sums are fp32.  In both, h_last / hidden / logits / margin
- *     are fp32 and token ids, lengths and indices are int32.
+ *     dtype HYDRA_BF16: weights are given as bfloat16; the KV cache holds 16-bit
+ *     elements and GEMM inputs are rounded to 16 bits (the library keeps these
+ *     as IEEE half, in which bfloat16 weights are exact); all sums are fp32.
+ *     In both, h_last / hidden / logits / margin are fp32 and token ids,
+ *     lengths and indices are int32.
  */
 #ifndef HYDRA_H
 #define HYDRA_H
@@ -101,7 +103,8 @@ typedef struct {
 } hydra_tree_desc;
 
 /* Paged KV cache, owned by the caller.  k_pages and v_pages each hold
- * n_layers * n_pages * H * 16 * Dh elements of the model dtype; page p of layer
+ * n_layers * n_pages * H * 16 * Dh elements (4 bytes each for HYDRA_F32, 2 bytes
+ * each for HYDRA_BF16); page p of layer
  * l, head h starts at element ((l * n_pages + p) * H + h) * 16 * Dh.  The
  * placement of (token, dim) inside a 16 x Dh block is private to the library
  * (it differs between K and V and between dtypes); callers move tokens only

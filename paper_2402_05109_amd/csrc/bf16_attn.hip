@@ -28,13 +28,11 @@
 
 namespace hydra {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
 
 // record of one workgroup in the partial buffer: O[Tq][Dh], m[Tq], l[Tq]   (Tq = 32 * ceil(T/32))
 __host__ __device__ inline size_t apart_record(int Tq, int Dh) { return (size_t)Tq * Dh + 2 * (size_t)Tq; }
@@ -45,7 +43,7 @@ template <int DH>
 struct KVTile { u32x4_t k[DH / 16]; u32x4_t v[2][DH / 32]; };
 
 template <int DH>
-__device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const bf16_t *kpages, const bf16_t *vpages,
+__device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const a16_t *kpages, const a16_t *vpages,
                                              const int32_t *pt, int t, int row_pages, int layer, int n_pages, int H,
                                              int h, int lane) {
     const int hl = lane >> 5, col = lane & 31;
@@ -64,7 +62,7 @@ __device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const bf16_t *kpage
 
 template <int DH, bool PACKED>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
-    const u32x4_t *__restrict__ qbuf, const bf16_t *__restrict__ kpages, const bf16_t *__restrict__ vpages,
+    const u32x4_t *__restrict__ qbuf, const a16_t *__restrict__ kpages, const a16_t *__restrict__ vpages,
     const int32_t *__restrict__ page_table, int max_pages, int n_pages, int layer, const int32_t *__restrict__ seq_len,
     const TreeDev *__restrict__ tree, int H, int QW, float scale, float *__restrict__ apart, void *out,
     int32_t *flags) {
@@ -132,8 +130,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
             for (int v = 0; v < 16; ++v) sc[v] = 0.f;
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.k[s]),
-                                                            __builtin_bit_cast(bf16x8_t, qreg[s]), sc, 0, 0, 0);
+                sc = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, cur.k[s]), __builtin_bit_cast(a16x8_t, qreg[s]), sc);
             const bool need_mask = slot0 + 32 > L;
             float cmax = -INFINITY;
 #pragma unroll
@@ -174,11 +171,10 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
             for (int g = 0; g < 2; ++g) {
                 u32x4_t pb;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) pb[w] = pack2bf(sc[8 * g + 2 * w], sc[8 * g + 2 * w + 1]);
+                for (int w = 0; w < 4; ++w) pb[w] = f2a_pack(sc[8 * g + 2 * w], sc[8 * g + 2 * w + 1]);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, cur.v[g][dt]),
-                                                                   __builtin_bit_cast(bf16x8_t, pb), o[dt], 0, 0, 0);
+                    o[dt] = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, cur.v[g][dt]), __builtin_bit_cast(a16x8_t, pb), o[dt]);
             }
             if (more) cur = nxt;
         }
@@ -231,8 +227,8 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
                 if (query < T) {
                     const int m = b * T + query;
                     if (PACKED) {
-                        u32x2_t pk = {pack2bf(acc[4 * g4] * inv, acc[4 * g4 + 1] * inv), pack2bf(acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv)};
-                        *reinterpret_cast<u32x2_t *>(reinterpret_cast<bf16_t *>(out) + x_index<true>(m, h * DH + dim, H * DH)) = pk;
+                        u32x2_t pk = {f2a_pack(acc[4 * g4] * inv, acc[4 * g4 + 1] * inv), f2a_pack(acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv)};
+                        *reinterpret_cast<u32x2_t *>(reinterpret_cast<a16_t *>(out) + x_index<true>(m, h * DH + dim, H * DH)) = pk;
                     } else {
                         f32x4_t v4 = {acc[4 * g4] * inv, acc[4 * g4 + 1] * inv, acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv};
                         *reinterpret_cast<f32x4_t *>(reinterpret_cast<float *>(out) + ((size_t)m * H + h) * DH + dim) = v4;
@@ -275,7 +271,7 @@ __global__ void attn_merge_kernel(const float *__restrict__ apart, const int32_t
             acc += __expf(r[(size_t)Tq * Dh + n] - mt) * r[(size_t)n * Dh + dim];
         }
         const int m = b * T + n;
-        if (PACKED) reinterpret_cast<bf16_t *>(out)[x_index<true>(m, h * Dh + dim, H * Dh)] = f2bf(acc * inv);
+        if (PACKED) reinterpret_cast<a16_t *>(out)[x_index<true>(m, h * Dh + dim, H * Dh)] = f2a(acc * inv);
         else        reinterpret_cast<float *>(out)[((size_t)m * H + h) * Dh + dim] = acc * inv;
     }
 }
@@ -314,11 +310,12 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     const int QTtot = ceil_div(T, 32);
     const int QW = QTtot >= 3 ? 4 : QTtot;                 // 1, 2 or 4 query waves
     const int KWV = ATTN_WAVES / QW;
-    // workgroups per (b, h): one unless the context is long (a key-split wave takes up to 16 tiles)
+    // workgroups per (b, h): a CU streams at most ~45 GB/s, so the keys of one head are spread over
+    // several CUs; a key-split wave takes about two 32-key tiles
     int wgs = 1;
     const int len = kv->seq_len_hint > 0 ? kv->seq_len_hint : c->m.max_pos;
     const int tiles = ceil_div(len + T, 32);
-    wgs = ceil_div(tiles, KWV * 16);
+    wgs = ceil_div(tiles, KWV * 2);
     if (wgs > units_max) wgs = units_max;
     if (wgs < 1) wgs = 1;
     dim3 grid(wgs, H, B), block(ATTN_WAVES * 64);
@@ -328,7 +325,7 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     const bool packed = x_out != nullptr;
 #define ATTN_CASE(DHv, Pv)                                                                                           \
     hipLaunchKernelGGL((attn_bf16_kernel<DHv, Pv>), grid, block, lds, s, (const u32x4_t *)qbuf,                       \
-                       (const bf16_t *)kv->k_pages, (const bf16_t *)kv->v_pages, kv->page_table, kv->max_pages,      \
+                       (const a16_t *)kv->k_pages, (const a16_t *)kv->v_pages, kv->page_table, kv->max_pages,      \
                        kv->n_pages, layer, seq_len, tree_dev(c), H, QW, scale, apart, out, flags)
     if (Dh == 128) { if (packed) ATTN_CASE(128, true); else ATTN_CASE(128, false); }
     else           { if (packed) ATTN_CASE(64, true); else ATTN_CASE(64, false); }

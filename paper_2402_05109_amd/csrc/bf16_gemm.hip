@@ -1,6 +1,8 @@
 // bf16 storage family: launch plans and epilogues of the weight-streaming GEMM
 // (kernel in gemm_bf16.h), and the kernels that bring plain row-major weights
 // into its tile order.
+#include <stdlib.h>
+
 #include "gemm_bf16.h"
 #include "internal.h"
 
@@ -66,13 +68,13 @@ struct EpiPlain {
 // contraction and is applied by the consumer) and ss[band][row] = sum over the
 // band's 32 columns of x^2.
 struct EpiResid {
-    float *x; int d; const float *gain; bf16_t *xg; float *ss; int Mpad;
+    float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad;
     template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
         float *__restrict__ xp = x;
-        bf16_t *__restrict__ xgp = xg;
+        a16_t *__restrict__ xgp = xg;
         float *__restrict__ ssp = ss;
         const int band = t.tile0 + i;
         const int col = band * 32 + (t.lane & 31);
@@ -90,7 +92,7 @@ struct EpiResid {
             float sq = 0.f;
             if (row < g.M) {
                 xp[(size_t)row * d + col] = xn;
-                xgp[x_index<true>(row, col, d)] = f2bf(xn * gn);
+                xgp[x_index<true>(row, col, d)] = f2a(xn * gn);
                 sq = xn * xn;
             }
 #pragma unroll
@@ -106,7 +108,7 @@ struct EpiResid {
 // feeds this GEMM.  Lanes of the left half finish rows v < 8 of a register set, lanes of the right
 // half rows v >= 8, each fetching the partner value from the lane 16 columns away.
 struct EpiSilu {
-    const float *ss; int nb; int Mpad; int dmodel; float eps; bf16_t *act; int F;
+    const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F;
     template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &t, const GemmGeom &, int wave) const {
         rstd_to_lds<MB>(t.lds, ss, nb, Mpad, t.mb0 * 32, dmodel, eps, t.lane, wave);
     }
@@ -116,7 +118,7 @@ struct EpiSilu {
         const int c = t.lane & 31;
         const bool left = c < 16;
         const int f = (t.tile0 + i) * 16 + (c & 15);
-        bf16_t *__restrict__ ap = act;
+        a16_t *__restrict__ ap = act;
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             // left lanes need (gate = own acc[v], up = partner acc[v]); right lanes (gate = partner acc[v+8], up = own acc[v+8])
@@ -127,14 +129,14 @@ struct EpiSilu {
             const int row = acc_row(t.mb0 + a, left ? v : v + 8, t.lane);
             if (row >= g.M) continue;
             const float r = t.lds[row - t.mb0 * 32];
-            ap[x_index<true>(row, f, F)] = f2bf(silu_f(r * gate) * (r * up));
+            ap[x_index<true>(row, f, F)] = f2a(silu_f(r * gate) * (r * up));
         }
     }
 };
 
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
-    const float *bias; float *z; int d; int residual; bf16_t *xg;
+    const float *bias; float *z; int d; int residual; a16_t *xg;
     template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
@@ -142,7 +144,7 @@ struct EpiBiasSilu {
         const int col = (t.tile0 + i) * 32 + (t.lane & 31);
         const float bv = bias[col];
         float *__restrict__ zp = z;
-        bf16_t *__restrict__ xgp = xg;
+        a16_t *__restrict__ xgp = xg;
         float zo[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -155,7 +157,7 @@ struct EpiBiasSilu {
             if (row >= g.M) continue;
             const float y = silu_f(acc[v] + bv) + zo[v];
             zp[(size_t)row * d + col] = y;
-            xgp[x_index<true>(row, col, d)] = f2bf(y);
+            xgp[x_index<true>(row, col, d)] = f2a(y);
         }
     }
 };
@@ -168,7 +170,17 @@ int gemm_npad(const hydra_ctx *c, int N) { return c->bf16 ? ceil_div(N, 32) * 32
 // 256 CUs.  So a plan wants ~256 equally loaded workgroups and X bytes <= W bytes per workgroup:
 // more bands per wave (NT) amortise X, and splitting K over workgroups (S) both adds workgroups and
 // shrinks the X slice each one reads.  S > 1 leaves S partial outputs for the consumer to add.
+static double env_or(const char *name, double dflt) {
+    const char *v = getenv(name);
+    return v ? atof(v) : dflt;
+}
+
 GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
+    // model constants; the environment overrides exist for tuning runs only
+    static const double cap_gbps = env_or("HYDRA_PLAN_CAP", 45.0);        // L1-miss bytes one CU can pull, GB/s
+    static const double hbm_tbps = env_or("HYDRA_PLAN_HBM", 6.0);         // achievable HBM stream, TB/s
+    static const double split_us = env_or("HYDRA_PLAN_SPLIT_US", 0.5);    // cost of reading one more partial back, us
+    static const int max_split = (int)env_or("HYDRA_PLAN_MAX_SPLIT", 8);
     GemmPlan p;
     p.splits = 1;
     if (!c->bf16) { p.mb = 1; p.nt = 1; p.nw = 1; p.kw = 1; p.kpw = K; return p; }
@@ -185,16 +197,16 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     double best_cost = 1e30;
     for (int nt = pairs ? 2 : 1; nt <= nt_max; nt += pairs ? 2 : 1) {
         const int groups = ceil_div(bands, nt);
-        for (int s = 1; s <= (may_split ? 8 : 1); ++s) {
-            if (KT / s < 32 && s > 1) break;
+        for (int s = 1; s <= (may_split ? max_split : 1); ++s) {
+            if (KT / s < 16 && s > 1) break;
             const int wgs = groups * s * mgroups;
             const int rounds = ceil_div(wgs, 256);                     // workgroups on the busiest CU
             const double w_bytes = (double)nt * 32 * K * 2 / s;         // per workgroup
             const double x_bytes = (double)p.mb * 32 * K * 2 / s;
-            double cost = rounds * (w_bytes + x_bytes) / 45e3;          // us at the per-CU limit
-            const double hbm = (double)N * K * 2 / 6.0e6;               // us at the HBM limit
+            double cost = rounds * (w_bytes + x_bytes) / (cap_gbps * 1e3);   // us at the per-CU limit
+            const double hbm = (double)N * K * 2 / (hbm_tbps * 1e6);         // us at the HBM limit
             if (cost < hbm) cost = hbm;
-            cost += (s > 1 ? 1.0 + 0.5 * s : 0.0);                      // reading S partials back costs a little
+            cost += (s > 1 ? 1.0 + split_us * s : 0.0);                      // reading S partials back costs a little
             if (cost < best_cost - 1e-9) { best_cost = cost; best_nt = nt; best_s = s; }
         }
     }
@@ -283,7 +295,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
 // the chip, as S partial outputs added by a small second kernel.
 __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
                                                           int ld, size_t split_stride, const float *__restrict__ gain,
-                                                          bf16_t *__restrict__ xg, float *__restrict__ ss, int Mpad,
+                                                          a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad,
                                                           int d) {
     const int m = blockIdx.y;
     const int k = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -295,8 +307,8 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, 
     }
     *reinterpret_cast<f32x4_t *>(x + (size_t)m * d + k) = a;
     const f32x4_t gn = *reinterpret_cast<const f32x4_t *>(gain + k);
-    const uint32_t lo = (uint32_t)f2bf(a[0] * gn[0]) | ((uint32_t)f2bf(a[1] * gn[1]) << 16);
-    const uint32_t hi = (uint32_t)f2bf(a[2] * gn[2]) | ((uint32_t)f2bf(a[3] * gn[3]) << 16);
+    const uint32_t lo = f2a_pack(a[0] * gn[0], a[1] * gn[1]);
+    const uint32_t hi = f2a_pack(a[2] * gn[2], a[3] * gn[3]);
     uint32_t *dst = reinterpret_cast<uint32_t *>(xg + x_index<true>(m, k, d));     // 4 consecutive k share an 8-run
     dst[0] = lo; dst[1] = hi;
     float sq = a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
@@ -314,26 +326,26 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
         int rc = launch_bf16<EpiPlain, false>(c, s, X, W, M, N, K, p, epi);
         if (rc) return rc;
         hipLaunchKernelGGL(resid_norm_kernel, dim3(ceil_div(N, 1024), M), dim3(256), 0, s, x, part, p.splits, npad, stride,
-                           gain, (bf16_t *)xg, ss, Mpad, N);
+                           gain, (a16_t *)xg, ss, Mpad, N);
         HYDRA_LAUNCH_CHECK("resid_norm_kernel");
         return HYDRA_OK;
     }
     p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
-    EpiResid epi{x, N, gain, (bf16_t *)xg, ss, Mpad};
+    EpiResid epi{x, N, gain, (a16_t *)xg, ss, Mpad};
     return launch_bf16<EpiResid, false>(c, s, X, W, M, N, K, p, epi);
 }
 
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act) {
     GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_FUSED);
-    EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (bf16_t *)act, F};
+    EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (a16_t *)act, F};
     return launch_bf16<EpiSilu, false>(c, s, X, W, M, 2 * F, K, p, epi);
 }
 
 int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
                           const float *bias, float *z, bool residual, void *xg) {
     GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
-    EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (bf16_t *)xg};
+    EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (a16_t *)xg};
     return launch_bf16<EpiBiasSilu, false>(c, s, X, W, M, N, K, p, epi);
 }
 
@@ -365,7 +377,7 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
 }
 
 // ---------------------------------------------------------------------------
-// Row-major [N][K] bf16 -> tile order.  Source row n goes to band
+// Row-major [N][K] bfloat16 -> tile order, converted to the a16 element (see device_common.h).  Source row n goes to band
 // tile_off + (n / rows_per_band) * tile_stride, column col_off + n % rows_per_band, so
 // several source matrices can share the bands of one packed matrix (q|k|v stacked band
 // after band; gate and up side by side inside every band with rows_per_band = 16).
@@ -387,7 +399,12 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__re
     const int n = band * rows_per_band + c;
     const int k = kt * 16 + (lane >> 5) * 8;
     u32x4_t v = {0u, 0u, 0u, 0u};
-    if (n < N) v = *reinterpret_cast<const u32x4_t *>(src + (size_t)n * K + k);
+    if (n < N) {
+        const u32x4_t raw = *reinterpret_cast<const u32x4_t *>(src + (size_t)n * K + k);     // 8 bfloat16
+#pragma unroll
+        for (int q = 0; q < 4; ++q)                                                          // -> 8 half (exact from 2^-17 up)
+            v[q] = f2a_pack(__uint_as_float(raw[q] << 16), __uint_as_float(raw[q] & 0xffff0000u));
+    }
     dst[((size_t)(tile_off + band * tile_stride) * KT + kt) * 64 + lane] = v;
 }
 

@@ -1,5 +1,14 @@
-// Device-side helpers shared by all kernels: bf16 conversion, the MFMA operand
+// Device-side helpers shared by all kernels: 16-bit conversions, the MFMA operand
 // order used for GEMM inputs, in-page placement of K and V, wave reductions.
+//
+// Number formats of the bf16 storage family.  Weights arrive as bfloat16.  Inside
+// the library every 16-bit value that feeds a matrix core (packed weights, GEMM
+// inputs, q, the KV cache, softmax probabilities) is held as IEEE half ("a16"):
+// a bfloat16 weight of magnitude >= 2^-17 is exactly representable in half, and
+// half keeps 11 significant bits of the activations where bfloat16 keeps 8, which
+// is what keeps a 32-layer forward inside the 2e-2 parity tolerance (rounding
+// every GEMM input to bfloat16 measured 4e-2 on the 7B shape).  Conversions
+// saturate at the largest finite half (65504).  Sums are fp32 throughout.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -19,11 +28,31 @@ __device__ __forceinline__ uint32_t f2bf_pack(float lo, float hi) {
 }
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// ---- a16: the 16-bit activation / cache / packed-weight element (IEEE half) ----
+typedef uint16_t a16_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 a16x8_t;      // one lane's MFMA operand
+#define HYDRA_MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+__device__ __forceinline__ float a16_sat(float f) { return fminf(fmaxf(f, -65504.f), 65504.f); }
+__device__ __forceinline__ a16_t f2a(float f) { return __builtin_bit_cast(a16_t, (_Float16)a16_sat(f)); }
+__device__ __forceinline__ uint32_t f2a_pack(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_;
+    typedef __attribute__((ext_vector_type(2))) _Float16 h16x2_;
+    const f32x2_ v = {a16_sat(lo), a16_sat(hi)};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h16x2_));
+}
+__device__ __forceinline__ float a2f(a16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
 template <bool BF> struct Elem;
 template <> struct Elem<true>  { typedef bf16_t type; static __device__ __forceinline__ float ld(const bf16_t *p, size_t i) { return bf2f(p[i]); }
                                  static __device__ __forceinline__ void st(bf16_t *p, size_t i, float v) { p[i] = f2bf(v); } };
 template <> struct Elem<false> { typedef float type;  static __device__ __forceinline__ float ld(const float *p, size_t i) { return p[i]; }
                                  static __device__ __forceinline__ void st(float *p, size_t i, float v) { p[i] = v; } };
+// Elem: the format weights are GIVEN in (bf16 / fp32).  Act: the format of activations and cache (a16 / fp32).
+template <bool BF> struct Act;
+template <> struct Act<true>  { typedef a16_t type; static __device__ __forceinline__ float ld(const a16_t *p, size_t i) { return a2f(p[i]); }
+                                static __device__ __forceinline__ void st(a16_t *p, size_t i, float v) { p[i] = f2a(v); } };
+template <> struct Act<false> { typedef float type; static __device__ __forceinline__ float ld(const float *p, size_t i) { return p[i]; }
+                                static __device__ __forceinline__ void st(float *p, size_t i, float v) { p[i] = v; } };
 
 // ---- GEMM input order ------------------------------------------------------
 // bf16 family: activations X[M][K] are stored as 32-row x 16-column tiles in

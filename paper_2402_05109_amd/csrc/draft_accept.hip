@@ -27,14 +27,14 @@ int launch_draft_root(hydra_ctx *c, hipStream_t s, int B, const int32_t *root, i
 template <bool BF>
 __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_root, const float *h_last,
                                     const int32_t *tree_tokens, const typename Elem<BF>::type *E, int d, int V,
-                                    int Kin, typename Elem<BF>::type *out, int32_t *flags) {
+                                    int Kin, typename Act<BF>::type *out, int32_t *flags) {
     const int ne = tree->n_expand[phase];
     const int r = blockIdx.x, seg = blockIdx.y;
     const int b = r / ne, j = r - b * ne;
     const int n = tree->expand_nodes[tree->expand_off[phase] + j];
     if (seg == 0) {
         for (int k = threadIdx.x; k < d; k += blockDim.x)
-            Elem<BF>::st(out, x_index<BF>(r, k, Kin), h_last[(size_t)b * d + k]);
+            Act<BF>::st(out, x_index<BF>(r, k, Kin), h_last[(size_t)b * d + k]);
         return;
     }
     // embedding of the path node at depth dd; n itself has depth phase-1
@@ -47,7 +47,7 @@ __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_
         tok = 0;
     }
     for (int k = threadIdx.x; k < d; k += blockDim.x)
-        out[x_index<BF>(r, seg * d + k, Kin)] = E[(size_t)tok * d + k];
+        Act<BF>::st(out, x_index<BF>(r, seg * d + k, Kin), Elem<BF>::ld(E, (size_t)tok * d + k));
 }
 
 int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const float *h_last,
@@ -58,7 +58,7 @@ int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const flo
     const int Kin = nseg * c->m.d;
     dim3 grid(B * ne, nseg), block(256);
     const void *E = c->arena + c->off_embed;
-    if (c->bf16) hipLaunchKernelGGL(draft_gather_kernel<true>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const bf16_t *)E, c->m.d, c->m.vocab, Kin, (bf16_t *)x_out, flags);
+    if (c->bf16) hipLaunchKernelGGL(draft_gather_kernel<true>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const bf16_t *)E, c->m.d, c->m.vocab, Kin, (a16_t *)x_out, flags);
     else         hipLaunchKernelGGL(draft_gather_kernel<false>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const float *)E, c->m.d, c->m.vocab, Kin, (float *)x_out, flags);
     HYDRA_LAUNCH_CHECK("draft_gather_kernel");
     return HYDRA_OK;
@@ -67,20 +67,20 @@ int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const flo
 // z <- (residual ? z : 0) + SiLU(W u + b);  also written as the next GEMM input
 template <bool BF>
 __global__ void bias_silu_kernel(const float *part, int S, int part_ld, size_t split_stride, const float *bias,
-                                 float *z, int residual, int d, typename Elem<BF>::type *out) {
+                                 float *z, int residual, int d, typename Act<BF>::type *out) {
     const int m = blockIdx.y;
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= d) return;
     float a = silu_f(part_sum(part, S, split_stride, (size_t)m * part_ld + k) + bias[k]);
     if (residual) a += z[(size_t)m * d + k];
     z[(size_t)m * d + k] = a;
-    Elem<BF>::st(out, x_index<BF>(m, k, d), a);
+    Act<BF>::st(out, x_index<BF>(m, k, d), a);
 }
 
 int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                      const float *bias, float *z, bool residual, void *x_out, int M) {
     dim3 grid(ceil_div(c->m.d, 256), M), block(256);
-    if (c->bf16) hipLaunchKernelGGL(bias_silu_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, bias, z, residual ? 1 : 0, c->m.d, (bf16_t *)x_out);
+    if (c->bf16) hipLaunchKernelGGL(bias_silu_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, bias, z, residual ? 1 : 0, c->m.d, (a16_t *)x_out);
     else         hipLaunchKernelGGL(bias_silu_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, bias, z, residual ? 1 : 0, c->m.d, (float *)x_out);
     HYDRA_LAUNCH_CHECK("bias_silu_kernel");
     return HYDRA_OK;
@@ -260,7 +260,7 @@ int launch_accept(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens
 template <bool BF>
 __global__ void compact_kernel(const TreeDev *tree, const int32_t *n_acc, const int32_t *path,
                                const int32_t *seq_len, const int32_t *page_table, int max_pages, int n_pages,
-                               typename Elem<BF>::type *kpages, typename Elem<BF>::type *vpages, int H, int Dh) {
+                               typename Act<BF>::type *kpages, typename Act<BF>::type *vpages, int H, int Dh) {
     const int h = blockIdx.x, layer = blockIdx.y, b = blockIdx.z;
     const int dim = threadIdx.x;
     if (dim >= Dh) return;
@@ -313,7 +313,7 @@ int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, con
                    const int32_t *next_root, const int32_t *last_node, const float *hidden, const hydra_kv *kv,
                    int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index) {
     dim3 grid(c->m.n_heads, c->m.n_layers, B), block(c->m.head_dim);
-    if (c->bf16) hipLaunchKernelGGL(compact_kernel<true>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, c->m.n_heads, c->m.head_dim);
+    if (c->bf16) hipLaunchKernelGGL(compact_kernel<true>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, c->m.n_heads, c->m.head_dim);
     else         hipLaunchKernelGGL(compact_kernel<false>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (float *)kv->k_pages, (float *)kv->v_pages, c->m.n_heads, c->m.head_dim);
     HYDRA_LAUNCH_CHECK("compact_kernel");
     hipLaunchKernelGGL(state_update_kernel, dim3(B), dim3(256), 0, s, tree_dev(c), n_acc, next_root, last_node, hidden, kv->page_table, kv->max_pages, c->m.d, seq_len, h_last, root, kv_index);

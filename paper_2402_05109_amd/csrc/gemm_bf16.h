@@ -3,7 +3,7 @@
 //   C[m][n] = sum_k X[m][k] * W[n][k]       fp32 accumulation
 //
 // At M <= 128 rows every weight byte is used once, so the kernel is a stream
-// over W that has to keep HBM busy.  W (N x K, bf16) is stored as 32 x 16
+// over W that has to keep HBM busy.  W (N x K, 16-bit) is stored as 32 x 16
 // (n x k) tiles of 1 KiB in the register order of the 32x32x16 MFMA "B" operand
 // (lane = (k%16)/8*32 + n%32 holds 8 consecutive k); the tiles of one 32-row
 // band are contiguous along k.  X uses the same tile order ("A" operand).
@@ -31,7 +31,6 @@
 
 namespace hydra {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -108,9 +107,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
                 for (int a = 0; a < MB; ++a)
 #pragma unroll
                     for (int i = 0; i < NT; ++i)
-                        acc[a][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, x[u][a]),
-                                                                          __builtin_bit_cast(bf16x8_t, w[u][i]),
-                                                                          acc[a][i], 0, 0, 0);
+                        acc[a][i] = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, x[u][a]), __builtin_bit_cast(a16x8_t, w[u][i]), acc[a][i]);
             }
         }
     };

@@ -39,7 +39,7 @@ __device__ __forceinline__ float row_rstd_block(const RowScale &rs, int m, float
 
 // bf16 family: x = E[token]; xg = bf16(x * gain) as GEMM input; ss[band][row] = sum of x^2 over the band
 __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const int32_t *tokens, float *x,
-                                                          const float *gain, bf16_t *xg, float *ss, int Mpad, int d,
+                                                          const float *gain, a16_t *xg, float *ss, int Mpad, int d,
                                                           int V, int32_t *flags) {
     const int m = blockIdx.x;
     int tok = tokens[m];
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
     for (int k = threadIdx.x; k < d; k += 256) {       // d is a multiple of 256 is not required: guarded below
         const float v = bf2f(E[(size_t)tok * d + k]);
         x[(size_t)m * d + k] = v;
-        xg[x_index<true>(m, k, d)] = f2bf(v * gain[k]);
+        xg[x_index<true>(m, k, d)] = f2a(v * gain[k]);
         float sq = v * v;
 #pragma unroll
         for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
 int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
                       float *ss, int Mpad, int M, int32_t *flags) {
     hipLaunchKernelGGL(embed_prep_kernel, dim3(M), dim3(256), 0, s, (const bf16_t *)(c->arena + c->off_embed), tokens, x,
-                       gain, (bf16_t *)xg, ss, Mpad, c->m.d, c->m.vocab, flags);
+                       gain, (a16_t *)xg, ss, Mpad, c->m.d, c->m.vocab, flags);
     HYDRA_LAUNCH_CHECK("embed_prep_kernel");
     return HYDRA_OK;
 }
@@ -98,7 +98,7 @@ int launch_embed(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, i
 template <bool BF>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *part, int S, int part_ld,
                                                        size_t split_stride, const float *gain, float eps, int d,
-                                                       typename Elem<BF>::type *out, float *hidden) {
+                                                       typename Act<BF>::type *out, float *hidden) {
     const int m = blockIdx.x;
     float v[32];
     float ss = 0.f;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *par
     cnt = 0;
     for (int k = threadIdx.x; k < d; k += 256, ++cnt) {
         const float y = v[cnt] * rstd * gain[k];
-        Elem<BF>::st(out, x_index<BF>(m, k, d), y);
+        Act<BF>::st(out, x_index<BF>(m, k, d), y);
         if (hidden) hidden[(size_t)m * d + k] = y;
     }
 }
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *x, const float *par
 int launch_rmsnorm(hydra_ctx *c, hipStream_t s, float *x, const float *part, int S, int part_ld,
                    size_t split_stride, const float *gain, void *x_out, int M, float *hidden_out) {
     if (c->m.d > 32 * 256) return fail(HYDRA_E_UNSUPPORTED, "rmsnorm: d > 8192");
-    if (c->bf16) hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(256), 0, s, x, part, S, part_ld, split_stride, gain, c->m.rms_eps, c->m.d, (bf16_t *)x_out, hidden_out);
+    if (c->bf16) hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(256), 0, s, x, part, S, part_ld, split_stride, gain, c->m.rms_eps, c->m.d, (a16_t *)x_out, hidden_out);
     else         hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(256), 0, s, x, part, S, part_ld, split_stride, gain, c->m.rms_eps, c->m.d, (float *)x_out, hidden_out);
     HYDRA_LAUNCH_CHECK("rmsnorm_kernel");
     return HYDRA_OK;
@@ -160,8 +160,8 @@ __device__ __forceinline__ size_t q_index(int b, int n, int h, int dim, int H, i
 template <bool BF>
 __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t split_stride, RowScale rs, const TreeDev *tree,
                                    const float *rope, const int32_t *seq_len, const int32_t *page_table,
-                                   int max_pages, int n_pages, int layer, typename Elem<BF>::type *kpages,
-                                   typename Elem<BF>::type *vpages, typename Elem<BF>::type *qbuf, int d, int H,
+                                   int max_pages, int n_pages, int layer, typename Act<BF>::type *kpages,
+                                   typename Act<BF>::type *vpages, typename Act<BF>::type *qbuf, int d, int H,
                                    int Dh, int max_pos, int32_t *flags) {
     const int T = tree->T;
     const int m = blockIdx.x, h = blockIdx.y;
@@ -185,15 +185,15 @@ __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t
     const float k0 = r * part_sum(part, S, split_stride, row + d + c0), k1 = r * part_sum(part, S, split_stride, row + d + c1);
     const float v0 = r * part_sum(part, S, split_stride, row + 2 * d + c0), v1 = r * part_sum(part, S, split_stride, row + 2 * d + c1);
     const float cs = rope[((size_t)pos * half + j) * 2], sn = rope[((size_t)pos * half + j) * 2 + 1];
-    Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
-    Elem<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
+    Act<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
+    Act<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
     const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
     const int tok = slot & 15;
     const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
-    Elem<BF>::st(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn);
-    Elem<BF>::st(kpages, base + k_in_block<BF>(tok, j + half, Dh), k1 * cs + k0 * sn);
-    Elem<BF>::st(vpages, base + v_in_block<BF>(tok, j, Dh), v0);
-    Elem<BF>::st(vpages, base + v_in_block<BF>(tok, j + half, Dh), v1);
+    Act<BF>::st(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn);
+    Act<BF>::st(kpages, base + k_in_block<BF>(tok, j + half, Dh), k1 * cs + k0 * sn);
+    Act<BF>::st(vpages, base + v_in_block<BF>(tok, j, Dh), v0);
+    Act<BF>::st(vpages, base + v_in_block<BF>(tok, j + half, Dh), v1);
 }
 
 int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
@@ -202,7 +202,7 @@ int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, in
     const int T = c->tree.T;
     dim3 grid(B * T, c->m.n_heads), block(64);
     if (c->bf16)
-        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (bf16_t *)kv->k_pages, (bf16_t *)kv->v_pages, (bf16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     else
         hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     HYDRA_LAUNCH_CHECK("rope_append_kernel");
@@ -211,16 +211,16 @@ int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, in
 
 // fp32 [B,T,H,Dh] q (already rotated) -> attention input buffer (tree_attention entry point)
 template <bool BF>
-__global__ void q_import_kernel(const float *q, typename Elem<BF>::type *qbuf, int T, int H, int Dh) {
+__global__ void q_import_kernel(const float *q, typename Act<BF>::type *qbuf, int T, int H, int Dh) {
     const int m = blockIdx.x, h = blockIdx.y;
     const int b = m / T, n = m - b * T;
     for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x)
-        Elem<BF>::st(qbuf, q_index<BF>(b, n, h, dim, H, Dh, T), q[(((size_t)m) * H + h) * Dh + dim]);
+        Act<BF>::st(qbuf, q_index<BF>(b, n, h, dim, H, Dh, T), q[(((size_t)m) * H + h) * Dh + dim]);
 }
 
 int launch_q_import(hydra_ctx *c, hipStream_t s, int B, const float *q_plain, void *qbuf) {
     dim3 grid(B * c->tree.T, c->m.n_heads), block(64);
-    if (c->bf16) hipLaunchKernelGGL(q_import_kernel<true>, grid, block, 0, s, q_plain, (bf16_t *)qbuf, c->tree.T, c->m.n_heads, c->m.head_dim);
+    if (c->bf16) hipLaunchKernelGGL(q_import_kernel<true>, grid, block, 0, s, q_plain, (a16_t *)qbuf, c->tree.T, c->m.n_heads, c->m.head_dim);
     else         hipLaunchKernelGGL(q_import_kernel<false>, grid, block, 0, s, q_plain, (float *)qbuf, c->tree.T, c->m.n_heads, c->m.head_dim);
     HYDRA_LAUNCH_CHECK("q_import_kernel");
     return HYDRA_OK;
@@ -234,7 +234,7 @@ int launch_q_import(hydra_ctx *c, hipStream_t s, int B, const float *q_plain, vo
 // ---------------------------------------------------------------------------
 template <bool BF>
 __global__ void silu_mul_kernel(const float *part, int S, int part_ld, size_t split_stride, int F, int blk,
-                                typename Elem<BF>::type *out) {
+                                typename Act<BF>::type *out) {
     const int m = blockIdx.y;
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
     if (f >= F) return;
@@ -242,14 +242,14 @@ __global__ void silu_mul_kernel(const float *part, int S, int part_ld, size_t sp
     const size_t row = (size_t)m * part_ld;
     const float g = part_sum(part, S, split_stride, row + gc);
     const float u = part_sum(part, S, split_stride, row + gc + blk);
-    Elem<BF>::st(out, x_index<BF>(m, f, F), silu_f(g) * u);
+    Act<BF>::st(out, x_index<BF>(m, f, F), silu_f(g) * u);
 }
 
 int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                     void *x_out, int M) {
     const int F = c->m.ffn;
     dim3 grid(ceil_div(F, 256), M), block(256);
-    if (c->bf16) hipLaunchKernelGGL(silu_mul_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, F, 16, (bf16_t *)x_out);
+    if (c->bf16) hipLaunchKernelGGL(silu_mul_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, F, 16, (a16_t *)x_out);
     else         hipLaunchKernelGGL(silu_mul_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, F, F, (float *)x_out);
     HYDRA_LAUNCH_CHECK("silu_mul_kernel");
     return HYDRA_OK;
@@ -307,7 +307,7 @@ int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int par
 // Plain [B][n_slots][2][H][Dh] fp32 <-> in-page cache placement (test harness).
 // ---------------------------------------------------------------------------
 template <bool BF, bool WRITE>
-__global__ void kv_plain_kernel(typename Elem<BF>::type *kpages, typename Elem<BF>::type *vpages,
+__global__ void kv_plain_kernel(typename Act<BF>::type *kpages, typename Act<BF>::type *vpages,
                                 const int32_t *page_table, int max_pages, int n_pages, int layer, int first_slot,
                                 int n_slots, int H, int Dh, float *plain) {
     const int b = blockIdx.z, i = blockIdx.x, h = blockIdx.y;
@@ -319,11 +319,11 @@ __global__ void kv_plain_kernel(typename Elem<BF>::type *kpages, typename Elem<B
     float *pv = plain + ((((size_t)b * n_slots + i) * 2 + 1) * H + h) * Dh;
     for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x) {
         if (WRITE) {
-            Elem<BF>::st(kpages, base + k_in_block<BF>(tok, dim, Dh), pk[dim]);
-            Elem<BF>::st(vpages, base + v_in_block<BF>(tok, dim, Dh), pv[dim]);
+            Act<BF>::st(kpages, base + k_in_block<BF>(tok, dim, Dh), pk[dim]);
+            Act<BF>::st(vpages, base + v_in_block<BF>(tok, dim, Dh), pv[dim]);
         } else {
-            pk[dim] = Elem<BF>::ld(kpages, base + k_in_block<BF>(tok, dim, Dh));
-            pv[dim] = Elem<BF>::ld(vpages, base + v_in_block<BF>(tok, dim, Dh));
+            pk[dim] = Act<BF>::ld(kpages, base + k_in_block<BF>(tok, dim, Dh));
+            pv[dim] = Act<BF>::ld(vpages, base + v_in_block<BF>(tok, dim, Dh));
         }
     }
 }
@@ -335,7 +335,7 @@ int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_k
 #define KVP(BFv, Wv, TY)                                                                                             \
     hipLaunchKernelGGL((kv_plain_kernel<BFv, Wv>), grid, block, 0, s, (TY *)kv->k_pages, (TY *)kv->v_pages,           \
                        kv->page_table, kv->max_pages, kv->n_pages, layer, first_slot, n_slots, H, Dh, plain)
-    if (c->bf16) { if (write_cache) KVP(true, true, bf16_t); else KVP(true, false, bf16_t); }
+    if (c->bf16) { if (write_cache) KVP(true, true, a16_t); else KVP(true, false, a16_t); }
     else         { if (write_cache) KVP(false, true, float); else KVP(false, false, float); }
 #undef KVP
     HYDRA_LAUNCH_CHECK("kv_plain_kernel");

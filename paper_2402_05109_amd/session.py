@@ -63,8 +63,9 @@ class Session:
         self.max_pages = (max_len + T_max + 15) // 16
         self.n_pages = B * self.max_pages
         n_el = shape.NL * self.n_pages * shape.H * 16 * shape.Dh
-        self.k_pages = torch.zeros(n_el, dtype=self.tdtype, device=self.dev)
-        self.v_pages = torch.zeros(n_el, dtype=self.tdtype, device=self.dev)
+        cache_dtype = torch.float16 if shape.dtype == "bf16" else torch.float32     # 2 or 4 bytes per element; content is private
+        self.k_pages = torch.zeros(n_el, dtype=cache_dtype, device=self.dev)
+        self.v_pages = torch.zeros(n_el, dtype=cache_dtype, device=self.dev)
         if page_perm_seed is None:
             perm = torch.arange(self.n_pages, dtype=torch.int32)
         else:

@@ -30,6 +30,11 @@ def bf16_round(a):
     return torch.tensor(a, dtype=torch.float32).to(torch.bfloat16).double().numpy()
 
 
+def cache_round(a):
+    """Values the 16-bit KV cache holds exactly (the library keeps them as IEEE half)."""
+    return torch.tensor(a, dtype=torch.float32).to(torch.float16).double().numpy()
+
+
 TREES = {"tiny16": lambda: frozen_tree("tiny16"), "prior64": lambda: frozen_tree("prior64"),
          "prior128": lambda: frozen_tree("prior128"), "prior32": lambda: frozen_tree("prior32"),
          "single": lambda: [-1], "chain40": lambda: chain_tree(40), "random70": lambda: random_tree(70, 4, 3)}
@@ -111,7 +116,7 @@ def test_kv_write_read_roundtrip_and_compact_bit_exact():
     rng = np.random.default_rng(4)
     caches = [O.FlatCache(m, L + T) for _ in range(B)]
     for c in caches:
-        c.K[:] = bf16_round(rng.standard_normal(c.K.shape)); c.V[:] = bf16_round(rng.standard_normal(c.V.shape))
+        c.K[:] = cache_round(rng.standard_normal(c.K.shape)); c.V[:] = cache_round(rng.standard_normal(c.V.shape))
     load_oracle_cache(sess, caches, L + T)
     sess.seq_len.fill_(L)
     back = read_cache(sess, sess.main, 0, L + T)
