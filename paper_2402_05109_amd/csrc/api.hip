@@ -269,9 +269,9 @@ int hydra_load_tensor(hydra_ctx *c, void *stream, int kind, int index, int sub, 
     if ((kind == HYDRA_W_HEAD_WL || kind == HYDRA_W_HEAD_BL) && (sub < 2 || sub > c->h.mlp_layers))
         return fail(HYDRA_E_INVALID_ARG, "MLP layer index out of range (2..mlp_layers)");
     auto matrix = [&](size_t off, int N, int K, int f32_row_off, int f32_rows_total, int tile_off, int tile_stride,
-                      int rows_per_band = 32, int col_off = 0) -> int {
+                      int rows_per_band = 32, int col_off = 0, int bands_per_head = 0) -> int {
         (void)f32_rows_total;
-        if (c->bf16) return launch_pack_matrix(c, s, src, A + off, N, K, tile_off, tile_stride, rows_per_band, col_off);
+        if (c->bf16) return launch_pack_matrix(c, s, src, A + off, N, K, tile_off, tile_stride, rows_per_band, col_off, bands_per_head);
         return launch_copy_matrix(c, s, src, A + off, N, K, f32_row_off, K);
     };
     switch (kind) {
@@ -280,8 +280,8 @@ int hydra_load_tensor(hydra_ctx *c, void *stream, int kind, int index, int sub, 
         case HYDRA_W_FINAL_NORM: return launch_to_f32(c, s, src, (float *)(A + c->off_final_norm), d);
         case HYDRA_W_ATTN_NORM:  return launch_to_f32(c, s, src, (float *)(A + c->layer[index].attn_norm), d);
         case HYDRA_W_FFN_NORM:   return launch_to_f32(c, s, src, (float *)(A + c->layer[index].ffn_norm), d);
-        case HYDRA_W_WQ:         return matrix(c->layer[index].wqkv, d, d, 0, 3 * d, 0, 1);
-        case HYDRA_W_WK:         return matrix(c->layer[index].wqkv, d, d, d, 3 * d, d / 32, 1);
+        case HYDRA_W_WQ:         return matrix(c->layer[index].wqkv, d, d, 0, 3 * d, 0, 1, 32, 0, c->m.head_dim / 32);        // bf16: rotary
+        case HYDRA_W_WK:         return matrix(c->layer[index].wqkv, d, d, d, 3 * d, d / 32, 1, 32, 0, c->m.head_dim / 32);   // pairs adjacent
         case HYDRA_W_WV:         return matrix(c->layer[index].wqkv, d, d, 2 * d, 3 * d, 2 * (d / 32), 1);
         case HYDRA_W_WO:         return matrix(c->layer[index].wo, d, d, 0, d, 0, 1);
         case HYDRA_W_GATE:       return matrix(c->layer[index].wgu, F, d, 0, 2 * F, 0, 1, 16, 0);     // bf16: left half of every band
@@ -407,8 +407,7 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
         for (int l = 0; l < c->m.n_layers; ++l) {
             const LayerOff &o = c->layer[l];
             const float *next_gain = (const float *)(A + (l + 1 < c->m.n_layers ? c->layer[l + 1].attn_norm : c->off_final_norm));
-            if ((rc = launch_gemm(c, s, xa, A + o.wqkv, part, M, 3 * d, d, &p))) return rc;
-            if ((rc = launch_rope_append(c, s, part, p.splits, ld_qkv, mp * ld_qkv, rs, B, l, seq_len, kv, qbuf, flags))) return rc;
+            if ((rc = launch_gemm_qkv_rope(c, s, xa, A + o.wqkv, M, rs, l, seq_len, kv, qbuf, flags))) return rc;
             if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xb, nullptr, flags))) return rc;
             if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad, part))) return rc;
             if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, d / 32, Mpad, xb))) return rc;

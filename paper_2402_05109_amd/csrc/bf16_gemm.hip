@@ -11,46 +11,78 @@ namespace hydra {
 // rows of a lane's accumulator registers
 __device__ __forceinline__ int acc_row(int mb, int v, int lane) { return mb * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
-// rstd[r] for the 32*MB rows of this row group, from the per-band sums of squares
-// ss[band][Mpad] left by the residual epilogue:  1 / sqrt(sum_band ss / d + eps).
-// All waves of the workgroup cooperate: wave w adds bands w, w + nwaves, ... for row = lane
-// (independent loads, one round trip), the partial sums meet in LDS in a fixed order.
+// Per-row 1/rms for the 32*MB rows of a workgroup, from the per-band sums of squares ss[band][Mpad]
+// left by the producer of the GEMM input:  rstd = 1 / sqrt(sum_band ss / d + eps).
+// The waves of the workgroup share the bands.  A load instruction covers G = 64 / (8*MB) bands: lane
+// l reads the four rows 4*(l % (8*MB)) .. +3 of band group l / (8*MB).  rowsum_issue() starts the
+// first eight such loads of a wave; rowsum_finish() adds them (and any further batches, which only
+// very wide models need), folds the band groups together with lane shuffles and leaves this wave's
+// partial sums in LDS at lds[wave*128 + row].  rstd_row() adds the partials in wave order.
+struct RowSumRegs { f32x4_t v[8]; };
+struct NoPre {};
+
 template <int MB>
-__device__ __forceinline__ void rstd_to_lds(float *lds, const float *__restrict__ ss, int nb, int Mpad, int row0, int d,
-                                            float eps, int lane, int wave) {
+__device__ __forceinline__ RowSumRegs rowsum_issue(const float *__restrict__ ss, int nb, int Mpad, int row0, int lane,
+                                                   int wave, int base) {
+    constexpr int LPR = 8 * MB, G = 64 / LPR;
     const int nwaves = blockDim.x >> 6;
-    float *partial = lds + 128;                               // [nwaves <= 8][up to 128 rows] would not fit: rows are done 64 at a time
-    for (int r0 = 0; r0 < 32 * MB; r0 += 64) {
-        const int r = r0 + lane;
-        float acc = 0.f;
-        if (r < 32 * MB) {
-            float v[16];
-            for (int b0 = wave; b0 < nb; b0 += 16 * nwaves) {
+    const int grp = lane / LPR, r4 = (lane % LPR) * 4;
+    RowSumRegs r;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int b = b0 + j * nwaves;
-                    v[j] = b < nb ? ss[(size_t)b * Mpad + row0 + r] : 0.f;
-                }
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc += v[j];
-            }
-        }
-        partial[wave * 64 + lane] = acc;
-        __syncthreads();
-        if (wave == 0 && r < 32 * MB) {
-            float t = 0.f;
-            for (int w = 0; w < nwaves; ++w) t += partial[w * 64 + lane];
-            lds[r] = 1.0f / sqrtf(t / (float)d + eps);
-        }
-        __syncthreads();
+    for (int j = 0; j < 8; ++j) {
+        const int b = base + (j * nwaves + wave) * G + grp;
+        if (b < nb) r.v[j] = *reinterpret_cast<const f32x4_t *>(ss + (size_t)b * Mpad + row0 + r4);
+        else        r.v[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    return r;
+}
+
+template <int MB>
+__device__ __forceinline__ void rowsum_finish(RowSumRegs r, float *lds, const float *__restrict__ ss, int nb, int Mpad,
+                                              int row0, int lane, int wave) {
+    constexpr int LPR = 8 * MB, G = 64 / LPR;
+    const int nwaves = blockDim.x >> 6;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0;;) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += r.v[j];
+        base += 8 * nwaves * G;
+        if (base >= nb) break;
+        r = rowsum_issue<MB>(ss, nb, Mpad, row0, lane, wave, base);
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+        acc[0] += __shfl_xor(acc[0], o, 64); acc[1] += __shfl_xor(acc[1], o, 64);
+        acc[2] += __shfl_xor(acc[2], o, 64); acc[3] += __shfl_xor(acc[3], o, 64);
+    }
+    if (lane < LPR) *reinterpret_cast<f32x4_t *>(lds + GEMM_LDS_ROWSUM + wave * 128 + lane * 4) = acc;
+}
+
+// after the barrier: every wave fills its own table of row scales, rstd[row] at wave_stage(t)[256 + row]
+__device__ __forceinline__ float *wave_stage(float *lds, int wave) { return lds + GEMM_LDS_STAGE + wave * GEMM_LDS_STAGE_WAVE; }
+template <int MB>
+__device__ __forceinline__ void rstd_table(float *lds, int lane, int wave, int d, float eps) {
+    const int nwaves = blockDim.x >> 6;
+    float *tab = wave_stage(lds, wave) + 256;
+    for (int r = lane; r < 32 * MB; r += 64) {
+        float s = 0.f;
+        for (int w = 0; w < nwaves; ++w) s += lds[GEMM_LDS_ROWSUM + w * 128 + r];
+        tab[r] = 1.0f / sqrtf(s / (float)d + eps);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // ---- epilogues (one 32x32 tile at a time; see gemm_bf16.h) -------------------------
 // out[split][row][col] = acc
 struct EpiPlain {
     float *out; int ld; size_t split_stride;
-    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
@@ -69,7 +101,11 @@ struct EpiPlain {
 // band's 32 columns of x^2.
 struct EpiResid {
     float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad;
-    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
@@ -109,16 +145,30 @@ struct EpiResid {
 // half rows v >= 8, each fetching the partner value from the lane 16 columns away.
 struct EpiSilu {
     const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F;
-    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &t, const GemmGeom &, int wave) const {
-        rstd_to_lds<MB>(t.lds, ss, nb, Mpad, t.mb0 * 32, dmodel, eps, t.lane, wave);
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = false;
+    template <int MB, int NT> __device__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+        return rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
     }
+    template <int MB, int NT> __device__ NoPre prologue(RowSumRegs r, const GemmTile<MB, NT> &t, const GemmGeom &) const {
+        rowsum_finish<MB>(r, t.lds, ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave);
+        return NoPre{};
+    }
+    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+        rstd_table<MB>(t.lds, t.lane, t.wave, dmodel, eps);
+    }
+    // One band of gate|up columns gives 32 rows x 16 features of the activation: exactly one 1 KiB tile of
+    // the next GEMM's input.  The wave assembles it in its LDS staging block and writes it with a single
+    // 16-byte-per-lane store (rows past M hold don't-care values in the padded part of the buffer).
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
-        const int c = t.lane & 31;
+        const int c = t.lane & 31, hl = t.lane >> 5;
         const bool left = c < 16;
-        const int f = (t.tile0 + i) * 16 + (c & 15);
-        a16_t *__restrict__ ap = act;
+        const int fo = c & 15;
+        float *ws = wave_stage(t.lds, t.wave);
+        a16_t *stage = reinterpret_cast<a16_t *>(ws);
+        const float *rstd = ws + 256 + a * 32 + 4 * hl;
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             // left lanes need (gate = own acc[v], up = partner acc[v]); right lanes (gate = partner acc[v+8], up = own acc[v+8])
@@ -126,18 +176,155 @@ struct EpiSilu {
             const float got = __shfl_xor(send, 16, 64);
             const float gate = left ? acc[v] : got;
             const float up = left ? got : acc[v + 8];
-            const int row = acc_row(t.mb0 + a, left ? v : v + 8, t.lane);
-            if (row >= g.M) continue;
-            const float r = t.lds[row - t.mb0 * 32];
-            ap[x_index<true>(row, f, F)] = f2a(silu_f(r * gate) * (r * up));
+            const int vv = left ? v : v + 8;
+            const int rl = 8 * (vv >> 2) + 4 * hl + (vv & 3);            // row inside the 32-row block
+            const float r = left ? rstd[8 * (v >> 2) + (v & 3)] : rstd[8 * ((v + 8) >> 2) + (v & 3)];
+            stage[((fo >> 3) * 32 + rl) * 8 + (fo & 7)] = f2a(silu_f(r * gate) * (r * up));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");           // LDS is in order within a wave; keep the compiler from reordering
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const u32x4_t blk = reinterpret_cast<const u32x4_t *>(stage)[t.lane];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        reinterpret_cast<u32x4_t *>(act)[((size_t)(t.mb0 + a) * (F >> 4) + (t.tile0 + i)) * 64 + t.lane] = blk;
+    }
+};
+
+// q|k|v projection with the rotary embedding and the cache append fused in (paper, section 2, "Tree
+// decoding": node n of row b sits at position seq_len[b] + depth[n] and its K/V go to slot seq_len[b] + n).
+// The q and k weight bands of a head are packed so that the bands holding dims j and j + Dh/2 are
+// neighbours: a band pair (NT = 2) then holds both members of every rotary pair in the same lane.  The
+// v bands keep their order.  r = 1/rms of the RMSNorm that feeds this GEMM (see rowsum_issue).
+// Wave 0 looks up position and cache page of the workgroup's rows while the weights stream and leaves
+// them in LDS: pos (or -1: row absent or over capacity), page*16 + slot%16, b*128 + n.
+struct QkvRopePre { RowSumRegs rs; int L[2]; int dep[2]; int max_depth; };
+struct QkvRopeCarry { int pos[2]; int pagetok[2]; int bn[2]; };
+struct EpiQkvRope {
+    const float *ss; int nb; int Mpad; int dmodel; float eps;
+    const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
+    a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = true;
+    template <int MB, int NT> __device__ QkvRopePre issue(const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        QkvRopePre p;
+        p.rs = rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
+        p.max_depth = 0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            p.L[q] = -1; p.dep[q] = 0;
+            const int r = t.lane + 64 * q, m = t.mb0 * 32 + r;
+            if (t.wave == 0 && r < 32 * MB && m < g.M) {
+                const int b = m / T, n = m - b * T;
+                p.L[q] = seq_len[b];
+                p.dep[q] = tree->depth[n];
+                p.max_depth = tree->max_depth;
+            }
+        }
+        return p;
+    }
+    template <int MB, int NT> __device__ QkvRopeCarry prologue(const QkvRopePre &p, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        rowsum_finish<MB>(p.rs, t.lds, ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave);
+        QkvRopeCarry c;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            c.pos[q] = -1; c.pagetok[q] = 0; c.bn[q] = 0;
+            const int r = t.lane + 64 * q, m = t.mb0 * 32 + r;
+            if (t.wave == 0 && r < 32 * MB && m < g.M) {
+                const int b = m / T, n = m - b * T, L = p.L[q];
+                const bool ok = L >= 0 && L + T <= max_pages * 16 && L + p.max_depth < max_pos;
+                if (ok) {
+                    const int slot = L + n;
+                    c.pos[q] = L + p.dep[q];
+                    c.pagetok[q] = page_table[(size_t)b * max_pages + (slot >> 4)] * 16 + (slot & 15);
+                    c.bn[q] = b * 128 + n;
+                } else if (blockIdx.x == 0) {
+                    atomicOr(flags, FLAG_CAPACITY);
+                }
+            }
+        }
+        return c;
+    }
+    template <int MB, int NT> __device__ void before_barrier(const QkvRopeCarry &c, const GemmTile<MB, NT> &t, const GemmGeom &) const {
+        if (t.wave != 0) return;
+        int *info = reinterpret_cast<int *>(t.lds + GEMM_LDS_ROWINFO);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int r = t.lane + 64 * q;
+            if (r < 32 * MB) { info[r] = c.pos[q]; info[128 + r] = c.pagetok[q]; info[256 + r] = c.bn[q]; }
         }
     }
+    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+        rstd_table<MB>(t.lds, t.lane, t.wave, dmodel, eps);
+    }
+    template <int MB, int NT>
+    __device__ void pair4(const float (&x0)[4], const float (&x1)[4], int a, int v0, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        if (t.tile0 + 1 >= g.NTiles) return;
+        const int c = t.lane & 31, hl = t.lane >> 5;
+        const int nbs = dmodel >> 5, bph = Dh >> 5, half = Dh >> 1;
+        const int sec = t.tile0 / nbs, hb = t.tile0 - sec * nbs;
+        const int h = hb / bph, pb = hb - h * bph;                       // pb is even: first band of a pair
+        const int *info = reinterpret_cast<const int *>(t.lds + GEMM_LDS_ROWINFO);
+        const float *rstd = wave_stage(t.lds, t.wave) + 256;
+        const int rl0 = a * 32 + 8 * (v0 >> 2) + 4 * hl;
+        int pos[4], pagetok[4], bn[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { pos[q] = info[rl0 + q]; pagetok[q] = info[128 + rl0 + q]; bn[q] = info[256 + rl0 + q]; }
+        a16_t *__restrict__ kp = kpages;
+        a16_t *__restrict__ vp = vpages;
+        a16_t *__restrict__ qp = qbuf;
+        if (sec == 2) {
+            const int dim0 = pb * 32 + c, dim1 = dim0 + 32;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (pos[q] < 0) continue;
+                const float r = rstd[rl0 + q];
+                const size_t base = kv_block_base(layer, n_pages, pagetok[q] >> 4, H, h, Dh);
+                const int tok = pagetok[q] & 15;
+                vp[base + v_in_block<true>(tok, dim0, Dh)] = f2a(r * x0[q]);
+                vp[base + v_in_block<true>(tok, dim1, Dh)] = f2a(r * x1[q]);
+            }
+            return;
+        }
+        const int j = (pb >> 1) * 32 + c;                                // rotary pair (j, j + Dh/2)
+        float cs[4], sn[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float2 t2 = pos[q] >= 0 ? *reinterpret_cast<const float2 *>(rope + ((size_t)pos[q] * half + j) * 2) : float2{1.f, 0.f};
+            cs[q] = t2.x; sn[q] = t2.y;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (pos[q] < 0) continue;
+            const float r = rstd[rl0 + q];
+            const float u0 = r * x0[q], u1 = r * x1[q];
+            const float y0 = u0 * cs[q] - u1 * sn[q], y1 = u1 * cs[q] + u0 * sn[q];
+            if (sec == 0) {
+                const int b = bn[q] >> 7, n = bn[q] & 127;
+                const int QT = (T + 31) >> 5, KS = Dh >> 4;
+                const size_t blk = (((size_t)b * H + h) * QT + (n >> 5)) * KS;
+                qp[(((blk + (j >> 4)) * 64 + ((j >> 3) & 1) * 32 + (n & 31)) << 3) + (j & 7)] = f2a(y0);
+                const int j1 = j + half;
+                qp[(((blk + (j1 >> 4)) * 64 + ((j1 >> 3) & 1) * 32 + (n & 31)) << 3) + (j1 & 7)] = f2a(y1);
+            } else {
+                const size_t base = kv_block_base(layer, n_pages, pagetok[q] >> 4, H, h, Dh);
+                const int tok = pagetok[q] & 15;
+                kp[base + k_in_block<true>(tok, j, Dh)] = f2a(y0);
+                kp[base + k_in_block<true>(tok, j + half, Dh)] = f2a(y1);
+            }
+        }
+    }
+    template <int MB, int NT>
+    __device__ void tile(const f32x16_t &, int, int, const GemmTile<MB, NT> &, const GemmGeom &) const {}
 };
 
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
     const float *bias; float *z; int d; int residual; a16_t *xg;
-    template <int MB, int NT> __device__ void prologue(GemmTile<MB, NT> &, const GemmGeom &, int) const {}
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
     __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
@@ -188,11 +375,11 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     p.mb = mblocks >= 4 ? 4 : (mblocks >= 2 ? 2 : 1);
     const int mgroups = ceil_div(mblocks, p.mb);
     const int bands = ceil_div(N, 32), KT = K / 16;
-    const bool pairs = false;
+    const bool pairs = kind == GEMM_KIND_PAIRS;                        // band pairs: exactly two bands per wave
     const bool may_split = kind == GEMM_KIND_PLAIN;
     p.nw = 1;
     // bands per wave: accumulators MB*NT*16 plus two prefetch sets must fit the register file
-    int nt_max = p.mb == 4 ? 2 : 4;
+    int nt_max = (p.mb == 4 || pairs) ? 2 : 4;
     int best_nt = pairs ? 2 : 1, best_s = 1;
     double best_cost = 1e30;
     for (int nt = pairs ? 2 : 1; nt <= nt_max; nt += pairs ? 2 : 1) {
@@ -229,7 +416,8 @@ static void launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t s, const G
     hipLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, g, epi);
 }
 
-template <class Epi, bool EVEN_ONLY>
+enum { NT_ANY = 0, NT_TWO = 2 };
+template <class Epi, int NT_SET>
 static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
                        const GemmPlan &p, const Epi &epi) {
     GemmGeom g;
@@ -246,12 +434,10 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
         HYDRA_HIP(hipEventRecord(e0, s));
     }
     const int key = p.mb * 10 + p.nt;
-    if constexpr (EVEN_ONLY) {
+    if constexpr (NT_SET == NT_TWO) {
         switch (key) {
             case 12: launch_one<1, 2>(grid, block, lds, s, g, epi); break;
-            case 14: launch_one<1, 4>(grid, block, lds, s, g, epi); break;
             case 22: launch_one<2, 2>(grid, block, lds, s, g, epi); break;
-            case 24: launch_one<2, 4>(grid, block, lds, s, g, epi); break;
             case 42: launch_one<4, 2>(grid, block, lds, s, g, epi); break;
             default: return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
         }
@@ -287,7 +473,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
     if (!c->bf16) return launch_gemm_f32(c, s, (const float *)X, (const float *)W, part, M, N, K);
     const int npad = gemm_npad(c, N);
     EpiPlain epi{part, npad, (size_t)ceil_div(M, 32) * 32 * npad};
-    return launch_bf16<EpiPlain, false>(c, s, X, W, M, N, K, p, epi);
+    return launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
 // x += X W^T, then xg = bf16(x * gain) and the per-band sums of squares.  Either fused into the GEMM
@@ -323,7 +509,7 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
         const int npad = gemm_npad(c, N);
         const size_t stride = (size_t)ceil_div(M, 32) * 32 * npad;
         EpiPlain epi{part, npad, stride};
-        int rc = launch_bf16<EpiPlain, false>(c, s, X, W, M, N, K, p, epi);
+        int rc = launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, N, K, p, epi);
         if (rc) return rc;
         hipLaunchKernelGGL(resid_norm_kernel, dim3(ceil_div(N, 1024), M), dim3(256), 0, s, x, part, p.splits, npad, stride,
                            gain, (a16_t *)xg, ss, Mpad, N);
@@ -332,21 +518,32 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
     }
     p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
     EpiResid epi{x, N, gain, (a16_t *)xg, ss, Mpad};
-    return launch_bf16<EpiResid, false>(c, s, X, W, M, N, K, p, epi);
+    return launch_bf16<EpiResid, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act) {
     GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_FUSED);
     EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (a16_t *)act, F};
-    return launch_bf16<EpiSilu, false>(c, s, X, W, M, 2 * F, K, p, epi);
+    return launch_bf16<EpiSilu, NT_ANY>(c, s, X, W, M, 2 * F, K, p, epi);
 }
 
 int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
                           const float *bias, float *z, bool residual, void *xg) {
     GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
     EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (a16_t *)xg};
-    return launch_bf16<EpiBiasSilu, false>(c, s, X, W, M, N, K, p, epi);
+    return launch_bf16<EpiBiasSilu, NT_ANY>(c, s, X, W, M, N, K, p, epi);
+}
+
+// q|k|v projection, rotary embedding and cache append in one kernel (bf16 family)
+int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, RowScale rs, int layer,
+                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags) {
+    const int d = c->m.d;
+    GemmPlan p = plan_gemm(c, M, 3 * d, d, GEMM_KIND_PAIRS);
+    EpiQkvRope epi{rs.ss, rs.nb, rs.Mpad, d, rs.eps, seq_len, tree_dev(c), kv->page_table, kv->max_pages, kv->n_pages, layer,
+                   (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, rope_dev(c), c->m.n_heads, c->m.head_dim,
+                   c->tree.T, c->m.max_pos, flags};
+    return launch_bf16<EpiQkvRope, NT_TWO>(c, s, X, W, M, 3 * d, d, p, epi);
 }
 
 template <int MB, int NT, class Epi>
@@ -372,6 +569,9 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
     if (e == hipSuccess) e = set_attr_all<EpiResid>();
     if (e == hipSuccess) e = set_attr_all<EpiBiasSilu>();
     if (e == hipSuccess) e = set_attr_all<EpiSilu>();
+    if (e == hipSuccess) e = set_attr<1, 2, EpiQkvRope>();
+    if (e == hipSuccess) e = set_attr<2, 2, EpiQkvRope>();
+    if (e == hipSuccess) e = set_attr<4, 2, EpiQkvRope>();
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(gemm_bf16_kernel)");
     return HYDRA_OK;
 }
@@ -381,11 +581,13 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
 // tile_off + (n / rows_per_band) * tile_stride, column col_off + n % rows_per_band, so
 // several source matrices can share the bands of one packed matrix (q|k|v stacked band
 // after band; gate and up side by side inside every band with rows_per_band = 16).
+// bph > 1 (q and k): within each group of bph bands (one head) the bands that hold the two
+// members of the rotary pairs (o and o + bph/2) are stored next to each other.
 // Columns of the last band that have no source row are zero.  One thread writes one
 // 16-byte lane entry.
 // ---------------------------------------------------------------------------
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__restrict__ dst, int N, int K,
-                                   int tile_off, int tile_stride, int rows_per_band, int col_off) {
+                                   int tile_off, int tile_stride, int rows_per_band, int col_off, int bph) {
     const int KT = K >> 4;
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // (band, kt, lane)
     const int nbands = (N + rows_per_band - 1) / rows_per_band;
@@ -405,15 +607,20 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__re
         for (int q = 0; q < 4; ++q)                                                          // -> 8 half (exact from 2^-17 up)
             v[q] = f2a_pack(__uint_as_float(raw[q] << 16), __uint_as_float(raw[q] & 0xffff0000u));
     }
-    dst[((size_t)(tile_off + band * tile_stride) * KT + kt) * 64 + lane] = v;
+    int dband = band;
+    if (bph > 1) {                      // rotary pairing: bands o and o + bph/2 of a head become neighbours
+        const int h = band / bph, o = band - h * bph, hb = bph >> 1;
+        dband = h * bph + (o % hb) * 2 + o / hb;
+    }
+    dst[((size_t)(tile_off + dband * tile_stride) * KT + kt) * 64 + lane] = v;
 }
 
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K, int tile_off,
-                       int tile_stride, int rows_per_band, int col_off) {
+                       int tile_stride, int rows_per_band, int col_off, int bph) {
     (void)c;
     const size_t total = (size_t)ceil_div(N, rows_per_band) * (K / 16) * 64;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)src,
-                       (u32x4_t *)dst, N, K, tile_off, tile_stride, rows_per_band, col_off);
+                       (u32x4_t *)dst, N, K, tile_off, tile_stride, rows_per_band, col_off, bph);
     HYDRA_LAUNCH_CHECK("pack_weight_kernel");
     return HYDRA_OK;
 }

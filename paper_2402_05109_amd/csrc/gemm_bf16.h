@@ -23,8 +23,16 @@
 // The epilogue is a functor with
 //   tile(acc, a, i, t, g): one finished 32x32 tile in the MFMA layout,
 //       acc[v] -> row = 32*(mb0+a) + 8*(v/4) + 4*(lane/32) + v%4,  col = 32*(tile0+i) + lane%32;
-//   prologue(t, g, wave): runs in every wave before streaming starts, after the
-//       first loads have been issued (used to prepare per-row scales in LDS).
+//   issue(t, g) / prologue(pre, t, g): run in every wave while the first two blocks of W are in
+//       flight: issue() only starts loads (returned in registers), prologue() consumes them after the
+//       second block has been requested and may start further loads whose registers it returns;
+//   before_barrier(carry, t, g): after streaming; receives what prologue() returned.  None of the
+//       three may contain a workgroup barrier; what they leave in LDS is visible to tile() because a
+//       barrier separates streaming from the epilogue;
+//   begin(t, g): once per wave after that barrier, before its first tile.
+// An epilogue with PAIRED = true (NT = 2) instead receives both tiles of a band pair, four accumulator
+// registers (rows) at a time:  pair4(x0, x1, a, v0, t, g) with x0[q], x1[q] the registers v0 + q of the
+// tiles (a, 0) and (a, 1).  The 4*MB such items of a band group are shared out over the KW waves.
 #pragma once
 
 #include "device_common.h"
@@ -44,7 +52,11 @@ struct GemmGeom {
     int NW, KW;     // waves per workgroup along N and K (KW a power of two)
 };
 
-enum { GEMM_LDS_SCRATCH = 128 + 8 * 64 };   // floats reserved in front of the reduction buffer: row scales + per-wave partials
+// floats reserved in front of the reduction buffer: per-wave partial row sums [8 waves][128 rows], then per
+// wave a 1 KiB staging block (epilogues that assemble whole operand tiles) and a 128-row table of row scales
+// and three 128-row tables of per-row integers shared by the workgroup
+enum { GEMM_LDS_ROWSUM = 0, GEMM_LDS_ROWINFO = 8 * 128, GEMM_LDS_STAGE = 8 * 128 + 3 * 128, GEMM_LDS_STAGE_WAVE = 256 + 128,
+       GEMM_LDS_SCRATCH = 8 * 128 + 3 * 128 + 8 * (256 + 128) };
 
 // prefetch distance in k-steps: two register sets of U*(NT+MB) KiB per wave
 template <int MB, int NT> struct GemmU { enum { value = (MB * NT >= 6) ? 4 : ((MB + NT >= 6) ? 2 : 4) }; };
@@ -53,7 +65,7 @@ template <int MB, int NT>
 struct GemmTile {
     int tile0;      // first band of this wave
     int mb0;        // first 32-row block
-    int lane;
+    int lane, wave;
     int split;      // blockIdx.y
     float *lds;     // GEMM_LDS_SCRATCH floats of per-workgroup scratch
 };
@@ -68,6 +80,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     t.tile0 = group * NT;
     t.mb0 = blockIdx.z * MB;
     t.lane = lane;
+    t.wave = wave;
     t.split = blockIdx.y;
     t.lds = red;
     float *redbuf = red + GEMM_LDS_SCRATCH;
@@ -121,27 +134,44 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
 #endif
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return k_begin + q * GEMM_U; };
     if (nblk > 0) load(wa, xa, kof(0));
-    epi.prologue(t, g, wave);                          // overlaps with the first loads
+    auto pre = epi.issue(t, g);
+    if (nblk > 1) load(wb, xb, kof(1));
+    auto carry = epi.prologue(pre, t, g);
     for (int j = 0; j < nblk; j += 2) {
-        if (j + 1 < nblk) load(wb, xb, kof(j + 1));
         compute(wa, xa, kof(j));
+        if (j + 2 < nblk) load(wa, xa, kof(j + 2));
         if (j + 1 < nblk) {
-            if (j + 2 < nblk) load(wa, xa, kof(j + 2));
             compute(wb, xb, kof(j + 1));
+            if (j + 3 < nblk) load(wb, xb, kof(j + 3));
         }
     }
 
     // ---- finish: KW == 1 keeps everything in registers; otherwise meet in LDS and share the tiles out
+    epi.before_barrier(carry, t, g);
     const bool live = t.tile0 < g.NTiles;                         // surplus waves streamed a clamped band: discard
+    constexpr int TILES = MB * NT;
     if (g.KW == 1) {
+        if (Epilogue::LDS_PROLOGUE && (g.NW > 1 || Epilogue::PAIRED)) __syncthreads();
         if (!live) return;
+        epi.begin(t, g);
+        if constexpr (Epilogue::PAIRED) {
 #pragma unroll
-        for (int a = 0; a < MB; ++a)
+            for (int a = 0; a < MB; ++a)
 #pragma unroll
-            for (int i = 0; i < NT; ++i) epi.tile(acc[a][i], a, i, t, g);
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float x0[4], x1[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) { x0[q] = acc[a][0][4 * q4 + q]; x1[q] = acc[a][NT - 1][4 * q4 + q]; }
+                    epi.pair4(x0, x1, a, 4 * q4, t, g);
+                }
+        } else {
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int i = 0; i < NT; ++i) epi.tile(acc[a][i], a, i, t, g);
+        }
         return;
     }
-    constexpr int TILES = MB * NT;
     {
         float *dst = redbuf + ((size_t)(kw * g.NW + nw) * TILES) * 16 * 64 + lane;
 #pragma unroll
@@ -153,22 +183,36 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     }
     __syncthreads();
     if (!live) return;
-#pragma unroll
-    for (int a = 0; a < MB; ++a)
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const int j = a * NT + i;
-            if (j % g.KW != kw) continue;                          // wave-uniform
-            f32x16_t sum;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+    epi.begin(t, g);
+    if constexpr (Epilogue::PAIRED) {
+        for (int id = kw; id < MB * 4; id += g.KW) {               // wave-uniform
+            const int a = id >> 2, v0 = (id & 3) * 4;
+            float x0[4] = {0.f, 0.f, 0.f, 0.f}, x1[4] = {0.f, 0.f, 0.f, 0.f};
             for (int w = 0; w < g.KW; ++w) {
-                const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + j) * 16 * 64 + lane;
+                const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + a * NT) * 16 * 64 + lane;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sum[v] += src[v * 64];
+                for (int q = 0; q < 4; ++q) { x0[q] += src[(v0 + q) * 64]; x1[q] += src[(16 * (NT - 1) + v0 + q) * 64]; }
             }
-            epi.tile(sum, a, i, t, g);
+            epi.pair4(x0, x1, a, v0, t, g);
         }
+    } else {
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                const int j = a * NT + i;
+                if (j % g.KW != kw) continue;                          // wave-uniform
+                f32x16_t sum;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+                for (int w = 0; w < g.KW; ++w) {
+                    const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + j) * 16 * 64 + lane;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sum[v] += src[v * 64];
+                }
+                epi.tile(sum, a, i, t, g);
+            }
+    }
 }
 
 }  // namespace hydra

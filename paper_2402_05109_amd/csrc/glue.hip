@@ -201,10 +201,9 @@ int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, in
                        int32_t *flags) {
     const int T = c->tree.T;
     dim3 grid(B * T, c->m.n_heads), block(64);
-    if (c->bf16)
-        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
-    else
-        hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+    // the bf16 family does this step in the epilogue of its q|k|v GEMM (launch_gemm_qkv_rope)
+    if (c->bf16) return fail(HYDRA_E_UNSUPPORTED, "rope_append: fp32 family only");
+    hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     HYDRA_LAUNCH_CHECK("rope_append_kernel");
     return HYDRA_OK;
 }

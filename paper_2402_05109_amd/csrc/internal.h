@@ -118,13 +118,15 @@ int gemm_max_dynamic_lds(hydra_ctx *c);
 int attn_max_dynamic_lds(hydra_ctx *c);
 // per-row 1/rms from the per-band sums of squares ss[band][Mpad] (bf16 family); ss == NULL: no scaling
 struct RowScale { const float *ss; int nb; int Mpad; int d; float eps; };
+int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, RowScale rs, int layer,
+                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags);
 int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
                       float *ss, int Mpad, int M, int32_t *flags);
 int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float *gain, RowScale rs, float *hidden, int M);
 
 // packing (arena loads)
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K,
-                       int tile_off, int tile_stride, int rows_per_band, int col_off);
+                       int tile_off, int tile_stride, int rows_per_band, int col_off, int bands_per_head);
 int launch_copy_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, size_t rows, size_t cols,
                        size_t dst_row_off, size_t dst_ld);
 int launch_to_f32(hydra_ctx *c, hipStream_t s, const void *src, float *dst, int n);
