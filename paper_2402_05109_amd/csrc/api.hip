@@ -353,10 +353,22 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
         if ((rc = launch_draft_gather(c, s, B, i, h_last, tree_tokens, xa, flags_ptr(c)))) return rc;
         void *cur = xb, *other = xa;
         if (c->bf16) {
-            // MLP layers with bias + SiLU (+ residual) fused into the GEMM epilogue
-            if ((rc = launch_gemm_bias_silu(c, s, xa, A + c->head[i].w1, Mi, d, Kin, (const float *)(A + c->head[i].b1), z, false, xb))) return rc;
+            // MLP layers: bias + SiLU (+ residual) fused into the GEMM epilogue, unless splitting K over more
+            // workgroups (with a small second kernel adding the partials) is estimated to be clearly faster:
+            // the wide first layer of the later heads has few output bands and a long K
+            auto mlp_layer = [&](const void *xin, size_t w_off, size_t b_off, int K, bool residual, void *xout) -> int {
+                const GemmPlan fused = plan_gemm(c, Mi, d, K, GEMM_KIND_FUSED), split = plan_gemm(c, Mi, d, K, GEMM_KIND_PLAIN);
+                if (split.splits > 1 && split.cost_us + 5.f < fused.cost_us) {
+                    int r2 = launch_gemm(c, s, xin, A + w_off, part, Mi, d, K, &p);
+                    if (r2) return r2;
+                    return launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), (size_t)align_up(Mi, 32) * gemm_npad(c, d),
+                                            (const float *)(A + b_off), z, residual, xout, Mi);
+                }
+                return launch_gemm_bias_silu(c, s, xin, A + w_off, Mi, d, K, (const float *)(A + b_off), z, residual, xout);
+            };
+            if ((rc = mlp_layer(xa, c->head[i].w1, c->head[i].b1, Kin, false, xb))) return rc;
             for (int j = 2; j <= c->h.mlp_layers; ++j) {
-                if ((rc = launch_gemm_bias_silu(c, s, cur, A + c->head[i].wl[j - 2], Mi, d, d, (const float *)(A + c->head[i].bl[j - 2]), z, true, other))) return rc;
+                if ((rc = mlp_layer(cur, c->head[i].wl[j - 2], c->head[i].bl[j - 2], d, true, other))) return rc;
                 std::swap(cur, other);
             }
         } else {

@@ -370,6 +370,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     static const int max_split = (int)env_or("HYDRA_PLAN_MAX_SPLIT", 8);
     GemmPlan p;
     p.splits = 1;
+    p.cost_us = 0.f;
     if (!c->bf16) { p.mb = 1; p.nt = 1; p.nw = 1; p.kw = 1; p.kpw = K; return p; }
     const int mblocks = ceil_div(M, 32);
     p.mb = mblocks >= 4 ? 4 : (mblocks >= 2 ? 2 : 1);
@@ -399,6 +400,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     }
     p.nt = best_nt;
     p.splits = best_s;
+    p.cost_us = (float)best_cost;
     const int max_waves = (p.mb * p.nt >= 6) ? 4 : 8;                   // 256-thread workgroups get 512 VGPRs per wave
     p.kw = max_waves;
     while (p.kw > 1 && KT / (p.kw * p.splits) < 4) p.kw >>= 1;

@@ -111,13 +111,10 @@ enum { TOPK_THREADS = 1024, TOPK_PER_LANE = 32 };
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, int S, int part_ld, size_t split_stride,
                                                              int V, const TreeDev *tree, int phase,
                                                              int32_t *tree_tokens) {
-    const int ne = tree->n_expand[phase];
     const int r = blockIdx.x;
-    const int b = r / ne, j = r - b * ne;
-    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
-    const int k = tree->n_children[n];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+    // the logits first: their addresses need nothing from the tree tables, whose dependent lookups follow
     float val[TOPK_PER_LANE];
     uint32_t live = 0;
 #pragma unroll
@@ -129,6 +126,10 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, i
             live |= 1u << i;
         }
     }
+    const int ne = tree->n_expand[phase];
+    const int b = r / ne, j = r - b * ne;
+    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
+    const int k = tree->n_children[n];
     __shared__ Cand surv[16 * HYDRA_MAX_TOPK];
     for (int t = 0; t < k; ++t) {
         Cand c = {-INFINITY, 0x7fffffff};

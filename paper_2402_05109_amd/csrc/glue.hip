@@ -47,14 +47,25 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
         if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
         tok = 0;
     }
-    for (int k = threadIdx.x; k < d; k += 256) {       // d is a multiple of 256 is not required: guarded below
-        const float v = bf2f(E[(size_t)tok * d + k]);
-        x[(size_t)m * d + k] = v;
-        xg[x_index<true>(m, k, d)] = f2a(v * gain[k]);
-        float sq = v * v;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    typedef __attribute__((ext_vector_type(4))) float f4;
+    // a thread takes 8 consecutive columns (d is a multiple of 128): one 16-byte load, one 16-byte store of xg
+    for (int k = threadIdx.x * 8; k < d; k += 256 * 8) {
+        const u4 raw = *reinterpret_cast<const u4 *>(E + (size_t)tok * d + k);
+        const f4 g0 = *reinterpret_cast<const f4 *>(gain + k), g1 = *reinterpret_cast<const f4 *>(gain + k + 4);
+        float v[8];
 #pragma unroll
-        for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
-        if ((threadIdx.x & 31) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
+        for (int q = 0; q < 4; ++q) { v[2 * q] = __uint_as_float(raw[q] << 16); v[2 * q + 1] = __uint_as_float(raw[q] & 0xffff0000u); }
+        *reinterpret_cast<f4 *>(x + (size_t)m * d + k) = f4{v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<f4 *>(x + (size_t)m * d + k + 4) = f4{v[4], v[5], v[6], v[7]};
+        const u4 pk = {f2a_pack(v[0] * g0[0], v[1] * g0[1]), f2a_pack(v[2] * g0[2], v[3] * g0[3]),
+                       f2a_pack(v[4] * g1[0], v[5] * g1[1]), f2a_pack(v[6] * g1[2], v[7] * g1[3])};
+        *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
+        float sq = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) sq += v[q] * v[q];
+        sq += __shfl_xor(sq, 1, 64); sq += __shfl_xor(sq, 2, 64);           // 4 threads = one 32-column band
+        if ((threadIdx.x & 3) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
     }
 }
 
@@ -268,36 +279,71 @@ __device__ __forceinline__ void top2_merge(Top2 &a, const Top2 &b) {
     else a.v2 = fmaxf(a.v2, b.v1);
 }
 
-__global__ __launch_bounds__(256) void argmax_kernel(const float *part, int S, int part_ld, size_t split_stride,
-                                                      RowScale rs, int V, int32_t *argmax, float *margin, float *logits) {
+// One workgroup of 1024 threads per row.  VEC: rows of `part` are 16-byte aligned (row stride a multiple
+// of 4), so a thread takes four consecutive logits per load and keeps four loads in flight.
+template <bool VEC>
+__global__ __launch_bounds__(1024) void argmax_kernel(const float *__restrict__ part, int S, int part_ld, size_t split_stride,
+                                                       RowScale rs, int V, int32_t *argmax, float *margin,
+                                                       float *__restrict__ logits) {
+    typedef __attribute__((ext_vector_type(4))) float f4;
     const int m = blockIdx.x;
     __shared__ float sh[1];
     const float r = row_rstd_block(rs, m, sh);
     Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
-    for (int v = threadIdx.x; v < V; v += 256) {
-        const float x = r * part_sum(part, S, split_stride, (size_t)m * part_ld + v);
-        if (logits) logits[(size_t)m * V + v] = x;
-        top2_push(t, x, v);
+    const float *row = part + (size_t)m * part_ld;
+    if (VEC) {
+        const int V4 = (V + 3) >> 2;                       // the last group may reach into the row padding (part_ld >= V rounded up to 4)
+        for (int g0 = threadIdx.x; g0 < V4; g0 += 4 * 1024) {
+            f4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * 1024;
+                x[u] = f4{0.f, 0.f, 0.f, 0.f};
+                if (g < V4)
+                    for (int sp = 0; sp < S; ++sp) x[u] += *reinterpret_cast<const f4 *>(row + (size_t)sp * split_stride + 4 * g);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * 1024;
+                if (g >= V4) continue;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int v = 4 * g + e;
+                    if (v >= V) continue;
+                    const float y = r * x[u][e];
+                    if (logits) logits[(size_t)m * V + v] = y;
+                    top2_push(t, y, v);
+                }
+            }
+        }
+    } else {
+        for (int v = threadIdx.x; v < V; v += 1024) {
+            const float x = r * part_sum(part, S, split_stride, (size_t)m * part_ld + v);
+            if (logits) logits[(size_t)m * V + v] = x;
+            top2_push(t, x, v);
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         Top2 u = {__shfl_xor(t.v1, o, 64), __shfl_xor(t.i1, o, 64), __shfl_xor(t.v2, o, 64)};
         top2_merge(t, u);
     }
-    __shared__ Top2 red[4];
+    __shared__ Top2 red[16];
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
     __syncthreads();
     if (threadIdx.x == 0) {
-        Top2 r = red[0];
-        for (int w = 1; w < 4; ++w) top2_merge(r, red[w]);
-        argmax[m] = r.i1;
-        if (margin) margin[m] = r.v1 - r.v2;
+        Top2 q = red[0];
+        for (int w = 1; w < 16; ++w) top2_merge(q, red[w]);
+        argmax[m] = q.i1;
+        if (margin) margin[m] = q.v1 - q.v2;
     }
 }
 
 int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, RowScale rs,
                   int M, int32_t *argmax, float *margin, float *logits) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(M), dim3(256), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
+    const bool vec = part_ld % 4 == 0 && split_stride % 4 == 0 && part_ld >= (c->m.vocab + 3) / 4 * 4;
+    if (vec) hipLaunchKernelGGL(argmax_kernel<true>, dim3(M), dim3(1024), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
+    else     hipLaunchKernelGGL(argmax_kernel<false>, dim3(M), dim3(1024), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
     HYDRA_LAUNCH_CHECK("argmax_kernel");
     return HYDRA_OK;
 }
