@@ -44,11 +44,8 @@ struct KVTile { u32x4_t k[DH / 16]; u32x4_t v[2][DH / 32]; };
 
 template <int DH>
 __device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const a16_t *kpages, const a16_t *vpages,
-                                             const int32_t *pt, int t, int row_pages, int layer, int n_pages, int H,
-                                             int h, int lane) {
+                                             int p0, int p1, int layer, int n_pages, int H, int h, int lane) {
     const int hl = lane >> 5, col = lane & 31;
-    const int p0 = pt[2 * t];
-    const int p1 = (2 * t + 1 < row_pages) ? pt[2 * t + 1] : p0;
     const u32x4_t *kp = reinterpret_cast<const u32x4_t *>(kpages + kv_block_base(layer, n_pages, (col >> 4) ? p1 : p0, H, h, DH));
 #pragma unroll
     for (int s = 0; s < DH / 16; ++s) kv.k[s] = kp[(2 * s + hl) * 16 + (col & 15)];
@@ -64,7 +61,7 @@ template <int DH, bool PACKED>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const u32x4_t *__restrict__ qbuf, const a16_t *__restrict__ kpages, const a16_t *__restrict__ vpages,
     const int32_t *__restrict__ page_table, int max_pages, int n_pages, int layer, const int32_t *__restrict__ seq_len,
-    const TreeDev *__restrict__ tree, int H, int QW, float scale, float *__restrict__ apart, void *out,
+    const TreeDev *__restrict__ tree, int T, int H, int QW, float scale, float *__restrict__ apart, void *out,
     int32_t *flags) {
     constexpr int KS = DH / 16, DT = DH / 32;
     extern __shared__ float lds[];
@@ -73,9 +70,31 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const int KWV = ATTN_WAVES / QW;
     const int qw = wave % QW, kwv = wave / QW;
     const int h = blockIdx.y, b = blockIdx.z;
-    const int T = tree->T;
     const int QTtot = (T + 31) >> 5;
     const int Tq = QTtot * 32;
+    const int units = gridDim.x * KWV;
+    const int unit = blockIdx.x * KWV + kwv;
+    const bool active = qw < QTtot;                        // idle waves only take part in the barriers
+    const int32_t *pt = page_table + (size_t)b * max_pages;
+    // Everything whose address does not depend on the row's length is requested before the length is known:
+    // the queries, the ancestor masks and the page-table entries of this wave's first two key tiles (the table
+    // has max_pages entries for every row, so the reads are in bounds; entries past the row's pages are not used).
+    u32x4_t qreg[KS];
+    uint64_t anc0 = 0ull, anc1 = 0ull;
+    int pg[2][2] = {{0, 0}, {0, 0}};
+    if (active) {
+        const size_t blk = (((size_t)b * H + h) * QTtot + qw) * KS;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qreg[s] = qbuf[(blk + s) * 64 + lane];
+        const int query = qw * 32 + col;
+        if (query < T) { anc0 = tree->anc[query][0]; anc1 = tree->anc[query][1]; }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int t = unit + j * units;
+            pg[j][0] = pt[min(2 * t, max_pages - 1)];
+            pg[j][1] = pt[min(2 * t + 1, max_pages - 1)];
+        }
+    }
     const int L = seq_len[b];
     if (L < 0 || L + T > max_pages * 16) {                 // uniform over the workgroup
         if (threadIdx.x == 0 && blockIdx.x == 0 && h == 0) atomicOr(flags, FLAG_CAPACITY);
@@ -84,10 +103,6 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const int total = L + T;
     const int n_tiles = (total + 31) >> 5;
     const int row_pages = (total + 15) >> 4;
-    const int units = gridDim.x * KWV;
-    const int unit = blockIdx.x * KWV + kwv;
-    const bool active = qw < QTtot;                        // idle waves only take part in the barriers
-    const int32_t *pt = page_table + (size_t)b * max_pages;
 
     f32x16_t o[DT];
 #pragma unroll
@@ -97,19 +112,19 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     float m_run = -INFINITY, l_run = 0.f;
 
     if (active && unit < n_tiles) {
-        u32x4_t qreg[KS];
-        const size_t blk = (((size_t)b * H + h) * QTtot + qw) * KS;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = qbuf[(blk + s) * 64 + lane];
-        const int query = qw * 32 + col;
-        const uint64_t anc0 = query < T ? tree->anc[query][0] : 0ull;
-        const uint64_t anc1 = query < T ? tree->anc[query][1] : 0ull;
-
         KVTile<DH> cur, nxt;
-        load_kv_tile<DH>(cur, kpages, vpages, pt, unit, row_pages, layer, n_pages, H, h, lane);
+        // second page of a tile: absent when the row ends inside the first one (its keys are masked; any valid page will do)
+        load_kv_tile<DH>(cur, kpages, vpages, pg[0][0], (2 * unit + 1 < row_pages) ? pg[0][1] : pg[0][0], layer, n_pages, H, h, lane);
         for (int t = unit; t < n_tiles; t += units) {
             const bool more = t + units < n_tiles;
-            if (more) load_kv_tile<DH>(nxt, kpages, vpages, pt, t + units, row_pages, layer, n_pages, H, h, lane);
+            if (more) {
+                const int tn = t + units;
+                int p0, p1;
+                if (t == unit) { p0 = pg[1][0]; p1 = pg[1][1]; }
+                else           { p0 = pt[2 * tn]; p1 = (2 * tn + 1 < row_pages) ? pt[2 * tn + 1] : p0; }
+                if (2 * tn + 1 >= row_pages) p1 = p0;
+                load_kv_tile<DH>(nxt, kpages, vpages, p0, p1, layer, n_pages, H, h, lane);
+            }
             const int slot0 = t * 32;
             if (slot0 + 32 > total) {   // zero V of slots >= total (stale or never written): 0 * garbage must not appear
 #pragma unroll
@@ -246,33 +261,53 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     }
 }
 
-// out[b, n, h, :] = sum_u w_u O_u[n] / sum_u w_u l_u,  w_u = exp(m_u - max_u m_u)
+// out[b, n, h, :] = sum_u w_u O_u[n] / sum_u w_u l_u,  w_u = exp(m_u - max_u m_u).
+// One workgroup per (row, head, 8 queries), one thread per (query, 4 dims); all loads of a thread are
+// independent of each other and of the row length, so they make one round trip.
+enum { MERGE_MAX_UNITS = 16 };
 template <bool PACKED>
-__global__ void attn_merge_kernel(const float *__restrict__ apart, const int32_t *__restrict__ seq_len, int T, int H,
-                                  int Dh, int units, int max_pages, void *out) {
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int L = seq_len[b];
-    if (L < 0 || L + T > max_pages * 16) return;
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ apart, const int32_t *__restrict__ seq_len,
+                                                          int T, int H, int Dh, int units, int max_pages, void *out) {
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int per_q = Dh >> 2;                              // threads per query
+    const int n = blockIdx.x * (256 / per_q) + threadIdx.x / per_q;
+    const int dim = (threadIdx.x % per_q) * 4;
     const int Tq = ((T + 31) >> 5) * 32;
     const size_t recsz = apart_record(Tq, Dh);
     const float *base = apart + (((size_t)b * H + h) * units) * recsz;
+    const bool live = n < T;
+    float mu[MERGE_MAX_UNITS], lu[MERGE_MAX_UNITS];
+    f32x4_t ou[MERGE_MAX_UNITS];
+#pragma unroll
+    for (int u = 0; u < MERGE_MAX_UNITS; ++u) {
+        mu[u] = -INFINITY; lu[u] = 0.f; ou[u] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (u < units && live) {
+            const float *r = base + u * recsz;
+            mu[u] = r[(size_t)Tq * Dh + n];
+            lu[u] = r[(size_t)Tq * Dh + Tq + n];
+            ou[u] = *reinterpret_cast<const f32x4_t *>(r + (size_t)n * Dh + dim);
+        }
+    }
+    const int L = seq_len[b];
+    if (L < 0 || L + T > max_pages * 16 || !live) return;
     float mt = -INFINITY;
-    for (int u = 0; u < units; ++u) mt = fmaxf(mt, base[u * recsz + (size_t)Tq * Dh + n]);
+#pragma unroll
+    for (int u = 0; u < MERGE_MAX_UNITS; ++u) mt = fmaxf(mt, mu[u]);
     float den = 0.f;
-    for (int u = 0; u < units; ++u) {
-        const float *r = base + u * recsz;
-        den += __expf(r[(size_t)Tq * Dh + n] - mt) * r[(size_t)Tq * Dh + Tq + n];
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < MERGE_MAX_UNITS; ++u) {
+        const float w = u < units ? __expf(mu[u] - mt) : 0.f;
+        den += w * lu[u];
+        acc += ou[u] * w;
     }
     const float inv = 1.0f / den;
-    for (int dim = threadIdx.x; dim < Dh; dim += blockDim.x) {
-        float acc = 0.f;
-        for (int u = 0; u < units; ++u) {
-            const float *r = base + u * recsz;
-            acc += __expf(r[(size_t)Tq * Dh + n] - mt) * r[(size_t)n * Dh + dim];
-        }
-        const int m = b * T + n;
-        if (PACKED) reinterpret_cast<a16_t *>(out)[x_index<true>(m, h * Dh + dim, H * Dh)] = f2a(acc * inv);
-        else        reinterpret_cast<float *>(out)[((size_t)m * H + h) * Dh + dim] = acc * inv;
+    const int m = b * T + n;
+    if (PACKED) {
+        u32x2_t pk = {f2a_pack(acc[0] * inv, acc[1] * inv), f2a_pack(acc[2] * inv, acc[3] * inv)};
+        *reinterpret_cast<u32x2_t *>(reinterpret_cast<a16_t *>(out) + x_index<true>(m, h * Dh + dim, H * Dh)) = pk;
+    } else {
+        *reinterpret_cast<f32x4_t *>(reinterpret_cast<float *>(out) + ((size_t)m * H + h) * Dh + dim) = acc * inv;
     }
 }
 
@@ -280,7 +315,7 @@ __global__ void attn_merge_kernel(const float *__restrict__ apart, const int32_t
 int attn_units(const hydra_ctx *c, int B) {
     int u = 512 / (B * c->m.n_heads);
     if (u < 1) u = 1;
-    if (u > 16) u = 16;
+    if (u > MERGE_MAX_UNITS) u = MERGE_MAX_UNITS;
     return u;
 }
 
@@ -326,13 +361,14 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
 #define ATTN_CASE(DHv, Pv)                                                                                           \
     hipLaunchKernelGGL((attn_bf16_kernel<DHv, Pv>), grid, block, lds, s, (const u32x4_t *)qbuf,                       \
                        (const a16_t *)kv->k_pages, (const a16_t *)kv->v_pages, kv->page_table, kv->max_pages,      \
-                       kv->n_pages, layer, seq_len, tree_dev(c), H, QW, scale, apart, out, flags)
+                       kv->n_pages, layer, seq_len, tree_dev(c), T, H, QW, scale, apart, out, flags)
     if (Dh == 128) { if (packed) ATTN_CASE(128, true); else ATTN_CASE(128, false); }
     else           { if (packed) ATTN_CASE(64, true); else ATTN_CASE(64, false); }
 #undef ATTN_CASE
     HYDRA_LAUNCH_CHECK("attn_bf16_kernel");
     if (wgs > 1) {
-        dim3 mgrid(T, H, B), mblock(Dh);
+        const int q_per_wg = 256 / (Dh / 4);
+        dim3 mgrid(ceil_div(T, q_per_wg), H, B), mblock(256);
         if (packed) hipLaunchKernelGGL(attn_merge_kernel<true>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, wgs, kv->max_pages, out);
         else        hipLaunchKernelGGL(attn_merge_kernel<false>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, wgs, kv->max_pages, out);
         HYDRA_LAUNCH_CHECK("attn_merge_kernel");
