@@ -120,7 +120,7 @@ def main():
     B, L0 = cfg.batch[0], cfg.prompt[0]
     spec = WeightSpec(cfg)
     dev = "cuda:0"
-    max_len = L0 + (args.steps + args.warmup + 8) * (cfg.K + 1)
+    max_len = L0 + (args.steps + args.warmup + 8 + 3 * 40) * (cfg.K + 1) + 2 * cfg.T
     sess = Session(cfg, parent, B, max_len, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=128)
     prompts = torch.stack([uniform_tokens(cfg.seed, b, L0, cfg.V) for b in range(B)])
     sess.prefill(prompts)
@@ -170,6 +170,38 @@ def main():
     ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
     traffic = read_traffic(args.config)
 
+    # throughput at injected acceptance lengths: between verify and accept, the base model's greedy token at the
+    # first j nodes of the left-most root-to-leaf path is overwritten with the drafted child token, so accept_greedy
+    # returns a fixed length (the generated text is then meaningless; only the cost of the step is real)
+    injected = []
+    kids = {}
+    for n, pa in enumerate(parent):
+        if pa >= 0 and pa not in kids:
+            kids[pa] = n
+    chain = [0]
+    while chain[-1] in kids:
+        chain.append(kids[chain[-1]])
+    sess.sync_len()
+    for a in sorted({2, 3, len(chain)}):
+        if a > len(chain) or sess.host_len + 40 * a + cfg.T + 8 > max_len:
+            continue
+        src = torch.tensor(chain[1:a], dtype=torch.long, device=dev)
+        dst = torch.tensor(chain[:a - 1], dtype=torch.long, device=dev)
+        n_steps = 32
+        o.argmax[:, dst] = o.tree_tokens[:, src]           # untimed: first use of the indexing kernels
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            sess.draft(); sess.verify()
+            o.argmax[:, dst] = o.tree_tokens[:, src]
+            if a < len(chain):
+                o.argmax[:, chain[a - 1]] = 1          # end of the injected path (a drafted child equal to token 1 is a 1-in-V accident)
+            sess.accept(); sess.compact()
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / n_steps
+        injected.append({"accept_len": a, "ms_per_step": t * 1e3, "tokens_per_s": a * B / t, "n_acc_check": int(o.n_acc[0])})
+        sess.sync_len()
+
     # autoregressive baseline with the same kernels (one-node tree)
     sess.ctx("ar")
     t_ar = timed(lambda: sess.step("ar"))
@@ -189,6 +221,7 @@ def main():
         "draft": {"ms": t_draft, "algorithmic_GB": draft_bytes(cfg) / 1e9, "GBps": draft_bytes(cfg) / (t_draft * 1e-3) / 1e9},
         "accept_compact_ms": t_tail,
         "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
+        "injected_acceptance": injected,
         "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",
                      "achieved": ach, "peak": peak, "unit": "GB/s", "frac": ach / peak, "traffic": traffic,
                      "launches_timed": n_launch, "avg_launch_us": ms_sum / max(n_launch, 1) * 1e3,
