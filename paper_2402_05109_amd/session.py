@@ -78,6 +78,12 @@ class Session:
         self.h_last = torch.zeros(B, shape.d, dtype=torch.float32, device=self.dev)
         self.root = torch.zeros(B, dtype=torch.int32, device=self.dev)
         self.host_len = 0                     # host upper bound on seq_len (hint only)
+        # the bound is tightened without stalling: every few steps seq_len is copied to pinned memory and picked
+        # up once the copy has landed
+        self._len_pinned = torch.zeros(B, dtype=torch.int32).pin_memory()
+        self._len_event: Optional[torch.cuda.Event] = None
+        self._growth_since_copy = 0
+        self._steps_since_copy = 0
         self.ws = torch.empty(max(self.main.workspace_bytes(B), 256), dtype=torch.uint8, device=self.dev)
 
     # ---- contexts -----------------------------------------------------------
@@ -137,6 +143,7 @@ class Session:
     def reset(self) -> None:
         self.seq_len.zero_(); self.h_last.zero_(); self.root.zero_()
         self.host_len = 0
+        self._len_event = None
 
     def prefill(self, prompts: torch.Tensor) -> None:
         """prompts: int32 [B, L] (same length for every row).  Causal chunks through
@@ -182,10 +189,12 @@ class Session:
         c.kv_compact(self.B, o.n_acc, o.path, o.next_root, o.last_node, o.hidden, self.kv, self.seq_len, self.h_last,
                      self.root, o.kv_index)
         self.host_len += c.depth + 1          # upper bound; the device holds the exact value
+        self._growth_since_copy += c.depth + 1
 
     def step(self, name: str = "main", hook=None) -> None:
         """One speculative step of every row.  `hook(outputs)` may edit tree_tokens between
         draft and verify (scripted-acceptance experiments)."""
+        self._refresh_bound()
         self.draft(name)
         if hook is not None:
             hook(self._out[name])
@@ -193,9 +202,24 @@ class Session:
         self.accept(name)
         self.compact(name)
 
+    def _refresh_bound(self, every: int = 8) -> None:
+        """Asynchronous tightening of the host bound on seq_len: no synchronisation, the value is used when it has arrived."""
+        if self._len_event is not None and self._len_event.query():
+            self.host_len = min(self.host_len, int(self._len_pinned.max()) + self._growth_since_copy)
+            self._len_event = None
+        self._steps_since_copy += 1
+        if self._len_event is None and self._steps_since_copy >= every:
+            self._len_pinned.copy_(self.seq_len, non_blocking=True)
+            self._len_event = torch.cuda.Event()
+            self._len_event.record()
+            self._growth_since_copy = 0
+            self._steps_since_copy = 0
+
     def sync_len(self) -> int:
         """Tighten the host bound from the device (synchronises)."""
         self.host_len = int(self.seq_len.max().item())
+        self._len_event = None
+        self._steps_since_copy = 0
         return self.host_len
 
     def generate(self, n_new: int, name: str = "main", max_steps: Optional[int] = None):
