@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--tree", type=int, default=0, choices=[0, 16, 32, 64, 128],
+                    help="candidate-tree size (nodes with the root); 0 = the configuration's own (the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
     args = ap.parse_args()
@@ -115,6 +117,8 @@ def main():
     cfg = CONFIGS[args.config]
     if args.layers:
         cfg = cfg.with_(NL=args.layers)
+    if args.tree:
+        cfg = cfg.with_(T=args.tree)
     tree_name = {16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T]
     parent = frozen_tree(tree_name)
     B, L0 = cfg.batch[0], cfg.prompt[0]
