@@ -173,6 +173,13 @@ def main():
     peak = 8000.0
     ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
     traffic = read_traffic(args.config)
+    # what an empty event bracket reads on this stream (the share of avg_launch_us that is not the kernel)
+    eb = []
+    for _ in range(50):
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a_.record(); b_.record(); b_.synchronize()
+        eb.append(a_.elapsed_time(b_))
+    empty_bracket_us = float(np.median(eb)) * 1e3
 
     # throughput at injected acceptance lengths: between verify and accept, the base model's greedy token at the
     # first j nodes of the left-most root-to-leaf path is overwritten with the drafted child token, so accept_greedy
@@ -230,6 +237,7 @@ def main():
                      "achieved": ach, "peak": peak, "unit": "GB/s", "frac": ach / peak, "traffic": traffic,
                      "launches_timed": n_launch, "avg_launch_us": ms_sum / max(n_launch, 1) * 1e3,
                      "algorithmic_bytes_per_launch": w_bytes / max(n_launch, 1),
+                     "empty_event_bracket_us": empty_bracket_us,
                      "scope": "the 129 GEMM launches of one tree_verify_forward (4 per layer + LM head), averaged over 8 calls"},
     }
     if not args.no_cpu_baseline:

@@ -383,8 +383,78 @@ def kv_compact(cache, L, path):
     return L + len(path)
 
 
-def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None):
-    """One full step.  Returns (emitted tokens, new L, new h_last, new root, info)."""
+# ----------------------------------------------------------------------------
+# Hydra++ prefix attention (paper, section 3.1 item 3; appendix, "Hydra-specific
+# prefix attention"): one more decoder layer on top of the base model whose only
+# role is to produce the hidden state the draft heads read.  It runs over the
+# verified sequence with its own K/V and is queried once per decoding step; the
+# heads take its representation of the last verified token in place of h_{t-1}.
+#
+# Readings (the paper does not fix them): the layer's input at position p is the
+# base model's hidden state of token p as the LM head sees it (after the final
+# RMSNorm); its output is the residual stream after the layer, with no further norm;
+# it is an ordinary pre-norm Llama decoder layer (weights "prefix.*") with rotary
+# positions 0, 1, 2, ...
+# ----------------------------------------------------------------------------
+class PrefixCache:
+    """K/V of the prefix-attention layer: [capacity, H, Dh], float64."""
+
+    def __init__(self, model, capacity):
+        self.K = np.zeros((capacity, model.H, model.Dh))
+        self.V = np.zeros((capacity, model.H, model.Dh))
+        self.capacity = capacity
+
+
+def prefix_token(model, pcache, x, pos):
+    """The prefix-attention layer on ONE hidden state x [d] at position pos
+    (pcache holds positions 0..pos-1).  Returns the layer's output [d]."""
+    m = model
+    x = np.asarray(x, dtype=np.float64)
+    n1 = rmsnorm(x, m.w("prefix.attn_norm"), m.eps)
+    q = rope((m.w("prefix.wq") @ n1).reshape(m.H, m.Dh), pos, m.theta)
+    k = rope((m.w("prefix.wk") @ n1).reshape(m.H, m.Dh), pos, m.theta)
+    pcache.K[pos] = k
+    pcache.V[pos] = (m.w("prefix.wv") @ n1).reshape(m.H, m.Dh)
+    att = np.zeros((m.H, m.Dh))
+    for h in range(m.H):
+        s = pcache.K[:pos + 1, h] @ q[h] / np.sqrt(m.Dh)
+        att[h] = softmax(s) @ pcache.V[:pos + 1, h]
+    a = x + m.w("prefix.wo") @ att.reshape(m.d)
+    n2 = rmsnorm(a, m.w("prefix.ffn_norm"), m.eps)
+    return a + m.w("prefix.w_down") @ (silu(m.w("prefix.w_gate") @ n2) * (m.w("prefix.w_up") @ n2))
+
+
+def prefix_chunk(model, pcache, L, X):
+    """The same layer on n consecutive hidden states X [n, d] at positions L..L+n-1
+    in one causally masked pass (what a chunked implementation computes).  Must equal
+    prefix_token applied one position at a time."""
+    m = model
+    X = np.asarray(X, dtype=np.float64)
+    n = X.shape[0]
+    N1 = rmsnorm(X, m.w("prefix.attn_norm"), m.eps)
+    Q = (N1 @ m.w("prefix.wq").T).reshape(n, m.H, m.Dh)
+    Kn = (N1 @ m.w("prefix.wk").T).reshape(n, m.H, m.Dh)
+    for j in range(n):
+        Q[j] = rope(Q[j], L + j, m.theta)
+        Kn[j] = rope(Kn[j], L + j, m.theta)
+    pcache.K[L:L + n] = Kn
+    pcache.V[L:L + n] = (N1 @ m.w("prefix.wv").T).reshape(n, m.H, m.Dh)
+    allowed = np.arange(L + n)[None, :] <= (L + np.arange(n))[:, None]
+    A = np.zeros((n, m.H, m.Dh))
+    for h in range(m.H):
+        S = np.where(allowed, Q[:, h] @ pcache.K[:L + n, h].T / np.sqrt(m.Dh), -np.inf)
+        A[:, h] = softmax(S) @ pcache.V[:L + n, h]
+    Y = X + A.reshape(n, m.d) @ m.w("prefix.wo").T
+    N2 = rmsnorm(Y, m.w("prefix.ffn_norm"), m.eps)
+    return Y + (silu(N2 @ m.w("prefix.w_gate").T) * (N2 @ m.w("prefix.w_up").T)) @ m.w("prefix.w_down").T
+
+
+def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None, pcache=None):
+    """One full step.  Returns (emitted tokens, new L, new h_last, new root, info).
+
+    With `pcache` (Hydra++ prefix attention) h_last is the prefix layer's output at the
+    last verified token: after acceptance the layer is fed the base hidden states of the
+    accepted tokens, one position each, and its last output becomes the new h_last."""
     tok, _ = draft_tree(model, tree, h_last, root)
     if draft_hook is not None:
         tok = draft_hook(tok)
@@ -393,19 +463,31 @@ def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None):
     emitted = [int(tok[n]) for n in path]
     L2 = kv_compact(cache, L, path)
     info = {"tok": tok, "argmax": amax, "path": path, "n_acc": n_acc, "logits": logits, "hidden": hidden}
-    return emitted, L2, hidden[last], next_root, info
+    h_new = hidden[last]
+    if pcache is not None:
+        for j, n in enumerate(path):
+            h_new = prefix_token(model, pcache, hidden[n], L + j)
+    return emitted, L2, h_new, next_root, info
 
 
-def hydra_generate(model, tree, prompt, n_new, draft_hook=None, capacity=None):
+def hydra_generate(model, tree, prompt, n_new, draft_hook=None, capacity=None, prefix=False):
     """Hydra decoding with greedy acceptance: the first n_new generated tokens
-    and the per-step acceptance lengths."""
+    and the per-step acceptance lengths.  prefix=True: Hydra++ prefix attention."""
     cap = capacity or (len(prompt) + n_new + tree.T + tree.max_depth + 2)
     cache = FlatCache(model, cap)
-    L, h_last, root, _ = ar_prefill(model, cache, prompt)
+    pcache = PrefixCache(model, cap) if prefix else None
+    if prefix:
+        h_last = logits = None
+        for pos, t in enumerate(prompt):
+            h, logits = ar_forward_token(model, cache, int(t), pos)
+            h_last = prefix_token(model, pcache, h, pos)
+        L, root = len(prompt), argmax_lowest(logits)
+    else:
+        L, h_last, root, _ = ar_prefill(model, cache, prompt)
     out, acc = [], []
     while len(out) < n_new:
         hook = (lambda t, _n=len(out): draft_hook(t, _n)) if draft_hook else None
-        emitted, L, h_last, root, info = hydra_step(model, cache, tree, L, h_last, root, hook)
+        emitted, L, h_last, root, info = hydra_step(model, cache, tree, L, h_last, root, hook, pcache)
         out += emitted
         acc.append(info["n_acc"])
     return out[:n_new], acc

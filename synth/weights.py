@@ -12,6 +12,7 @@ Tensor names and shapes (row-major, [out_features, in_features]):
     heads.I.w1 [d,(I+1)d]  (or [d, I*d] without the root embedding), heads.I.b1 [d]
     heads.I.wJ [d,d], heads.I.bJ [d]  for J = 2..mlp_layers
     heads.I.wout [V,d]                                   I = 1..K
+    prefix.<same nine names as a decoder layer>          when the configuration has the prefix-attention layer
 """
 from __future__ import annotations
 
@@ -44,6 +45,8 @@ def tensor_names(cfg: ModelShape) -> list:
         for j in range(2, cfg.mlp_layers + 1):
             names += [f"heads.{i}.w{j}", f"heads.{i}.b{j}"]
         names.append(f"heads.{i}.wout")
+    if cfg.prefix:
+        names += [f"prefix.{t}" for t in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
     return names
 
 
@@ -60,9 +63,13 @@ def _tensor_id_and_shape(spec: WeightSpec, name: str):
         return 2, (c.V, c.d), "matrix"
     if name == "final_norm":
         return 3, (c.d,), "gain"
-    if parts[0] == "layers":
-        l, t = int(parts[1]), parts[2]
-        tid = 1000 + l * 16 + _LAYER_SLOT[t]
+    if parts[0] in ("layers", "prefix"):
+        if parts[0] == "layers":
+            l, t = int(parts[1]), parts[2]
+            tid = 1000 + l * 16 + _LAYER_SLOT[t]
+        else:
+            t = parts[1]
+            tid = 500 + _LAYER_SLOT[t]
         if t in ("attn_norm", "ffn_norm"):
             return tid, (c.d,), "gain"
         if t in ("wq", "wk", "wv", "wo"):
