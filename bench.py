@@ -147,29 +147,39 @@ def main():
     L_end = sess.sync_len()
 
     # per-call latencies at the end-of-run context length (seq_len restored after each step)
+    def snapshot():
+        return (sess.seq_len.clone(), sess.h_last.clone(), sess.root.clone(), sess.host_len,
+                sess.pseq_len.clone() if sess.prefix else None)
+
+    def restore(saved):
+        sess.seq_len.copy_(saved[0]); sess.h_last.copy_(saved[1]); sess.root.copy_(saved[2]); sess.host_len = saved[3]
+        if sess.prefix:
+            sess.pseq_len.copy_(saved[4])
+
     def timed(fn, reps=20):
-        saved = (sess.seq_len.clone(), sess.h_last.clone(), sess.root.clone(), sess.host_len)
+        saved = snapshot()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ts = []
         for _ in range(reps):
             ev0.record(); fn(); ev1.record(); ev1.synchronize()
             ts.append(ev0.elapsed_time(ev1))
-            sess.seq_len.copy_(saved[0]); sess.h_last.copy_(saved[1]); sess.root.copy_(saved[2]); sess.host_len = saved[3]
+            restore(saved)
         return float(np.median(ts))
 
     t_draft = timed(sess.draft)
     t_verify = timed(sess.verify)
     t_tail = timed(lambda: (sess.accept(), sess.compact()))
+    t_prefix = timed(sess.prefix_attention) if sess.prefix else None
     vb = verify_bytes(cfg, B, L_end, cfg.T)
 
     # dominant kernel: the weight-streaming GEMM.  HIP events (recorded by the library on the launch stream)
     # around every GEMM launch of 8 tree_verify_forward calls at the end-of-run context length.
-    saved = (sess.seq_len.clone(), sess.h_last.clone(), sess.root.clone(), sess.host_len)
+    saved = snapshot()
     sess.main.profile_begin()
     for _ in range(8):
         sess.verify()
     n_launch, ms_sum, w_bytes = sess.main.profile_end()
-    sess.seq_len.copy_(saved[0]); sess.h_last.copy_(saved[1]); sess.root.copy_(saved[2]); sess.host_len = saved[3]
+    restore(saved)
     peak = 8000.0
     ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
     traffic = read_traffic(args.config)
@@ -207,7 +217,13 @@ def main():
             o.argmax[:, dst] = o.tree_tokens[:, src]
             if a < len(chain):
                 o.argmax[:, chain[a - 1]] = 1          # end of the injected path (a drafted child equal to token 1 is a 1-in-V accident)
-            sess.accept(); sess.compact()
+            sess.accept()
+            pre = sess.host_len
+            sess.compact()
+            if sess.prefix:
+                post, sess.host_len = sess.host_len, pre
+                sess.prefix_attention()
+                sess.host_len = post
         torch.cuda.synchronize()
         t = (time.perf_counter() - t0) / n_steps
         injected.append({"accept_len": a, "ms_per_step": t * 1e3, "tokens_per_s": a * B / t, "n_acc_check": int(o.n_acc[0])})
@@ -223,7 +239,7 @@ def main():
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights, f16 activations and KV cache, f32 accumulation" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg.name} shape d={cfg.d} NL={cfg.NL} H={cfg.H}x{cfg.Dh} F={cfg.F} V={cfg.V}, "
-                               f"{cfg.K} Hydra heads x {cfg.mlp_layers}-layer MLP, tree {tree_name} (T={cfg.T}), B={B}, "
+                               f"{cfg.K} Hydra heads x {cfg.mlp_layers}-layer MLP{' + prefix-attention layer' if cfg.prefix else ''}, tree {tree_name} (T={cfg.T}), B={B}, "
                                f"prompt {L0} uniform tokens, paged KV (16), natural acceptance",
                    "tokens_generated": tokens, "mean_acceptance": tokens / (args.steps * B), "context_at_end": L_end,
                    "device_flags": flags},
@@ -231,6 +247,7 @@ def main():
                    "frac_of_8TBps": vb / (t_verify * 1e-3) / 8e12, "context": L_end},
         "draft": {"ms": t_draft, "algorithmic_GB": draft_bytes(cfg) / 1e9, "GBps": draft_bytes(cfg) / (t_draft * 1e-3) / 1e9},
         "accept_compact_ms": t_tail,
+        "prefix_attention_ms": t_prefix,
         "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
         "injected_acceptance": injected,
         "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",

@@ -173,7 +173,9 @@ size_t hydra_workspace_bytes(const hydra_ctx *ctx, int B);
 /* Device-side flags raised by kernels of this context since the last call of
  * this function (or since hydra_bind_weights): bit 0 = a row's seq_len + T
  * exceeded its page table or max_pos (row skipped), bit 1 = a token id outside
- * [0, V) (treated as 0).  Reads and clears them; synchronises the stream. */
+ * [0, V) (treated as 0), bit 2 = hydra_prefix_attention met an n_acc outside
+ * [1, P] or a path entry outside [0, T_src) (clamped).  Reads and clears them;
+ * synchronises the stream. */
 int hydra_read_flags(hydra_ctx *ctx, void *stream, int32_t *flags_out /* host */);
 
 /* ---- the hot path -------------------------------------------------------- */
@@ -231,6 +233,30 @@ int kv_compact(hydra_ctx *ctx, void *stream, int B,
                const int32_t *n_acc, const int32_t *path, const int32_t *next_root,
                const int32_t *last_node, const float *hidden, const hydra_kv *kv,
                int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index);
+
+/* Section 3.1 item 3 and the appendix paragraph "Hydra-specific prefix
+ * attention" (Hydra++): an extra decoder layer over the verified sequence,
+ * queried once per decoding step, whose output at the last verified token the
+ * draft heads read in place of the base model's hidden state.
+ * `ctx` is a context of its own whose decoder layers are the prefix layer(s)
+ * (n_layers = 1 in the paper; its embedding, LM head and draft heads are never
+ * read), created with a chain tree of P nodes, with its own weight arena, KV
+ * cache and seq_len.  Per row b, with a = n_acc[b] in [1, P]: position
+ * seq_len[b] + j (j < a) is fed hidden[b, path[b, j]], the base model's hidden
+ * state after its final RMSNorm; its K/V go to slot seq_len[b] + j of `kv`.
+ * Then h_out[b] = the residual stream after the layer at position
+ * seq_len[b] + a - 1 (no further norm) and seq_len[b] += a.  Rows j >= a are
+ * computed on a copy of row a-1 and land in slots past the new length.
+ *   hidden  device [B, T_src, d] fp32 (tree_verify_forward's output)
+ *   path    device [B, P] int32       n_acc device [B] int32
+ *   seq_len device [B] int32 (in/out) h_out device [B, d] fp32 (out)
+ * After accept_greedy of a tree of depth Dmax use P = Dmax + 1 and its path;
+ * for a prefill chunk of n tokens use P = n, path = 0..n-1, n_acc = n.
+ * Readings of the paper taken here: input after the final norm, output before
+ * any norm, rotary positions equal to the base model's. */
+int hydra_prefix_attention(hydra_ctx *ctx, void *stream, int B, void *ws,
+                           const float *hidden, int T_src, const int32_t *path, const int32_t *n_acc,
+                           int32_t *seq_len, const hydra_kv *kv, float *h_out);
 
 /* ---- helpers for tests and harnesses -------------------------------------- */
 

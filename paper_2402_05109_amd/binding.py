@@ -24,7 +24,7 @@ E_INVALID_ARG, E_SHAPE, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_STATE = -1, -2, -3, 
 
 EXPORTS = ["hydra_create", "hydra_destroy", "hydra_last_error", "hydra_weights_bytes", "hydra_bind_weights",
            "hydra_load_tensor", "hydra_workspace_bytes", "hydra_read_flags", "hydra_draft_tree",
-           "tree_verify_forward", "tree_attention", "accept_greedy", "kv_compact", "hydra_tree_depth",
+           "tree_verify_forward", "tree_attention", "accept_greedy", "kv_compact", "hydra_prefix_attention", "hydra_tree_depth",
            "hydra_kv_write", "hydra_kv_read", "hydra_profile_begin", "hydra_profile_end"]
 
 
@@ -72,6 +72,7 @@ def _load() -> C.CDLL:
     lib.tree_attention.argtypes = [vp, vp, i32, i32, vp, vp, vp, C.POINTER(KVDesc), vp]
     lib.accept_greedy.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.kv_compact.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, C.POINTER(KVDesc), vp, vp, vp, vp]
+    lib.hydra_prefix_attention.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, C.POINTER(KVDesc), vp]
     lib.hydra_tree_depth.argtypes = [vp]
     lib.hydra_kv_write.argtypes = [vp, vp, i32, i32, C.POINTER(KVDesc), i32, i32, vp]
     lib.hydra_kv_read.argtypes = [vp, vp, i32, i32, C.POINTER(KVDesc), i32, i32, vp]
@@ -201,6 +202,13 @@ class Hydra:
                                _ptr(hidden, torch.float32, "hidden"), C.byref(d), _ptr(seq_len, torch.int32, "seq_len"),
                                _ptr(h_last, torch.float32, "h_last"), _ptr(root, torch.int32, "root"),
                                _ptr(kv_index, torch.int32, "kv_index")))
+
+    def hydra_prefix_attention(self, B, ws, hidden, T_src, path, n_acc, seq_len, kv: KV, h_out) -> None:
+        d = kv.desc()
+        _check(_lib.hydra_prefix_attention(self._h, _stream(), B, _ptr(ws, torch.uint8, "workspace"),
+                                           _ptr(hidden, torch.float32, "hidden"), T_src, _ptr(path, torch.int32, "path"),
+                                           _ptr(n_acc, torch.int32, "n_acc"), _ptr(seq_len, torch.int32, "seq_len"),
+                                           C.byref(d), _ptr(h_out, torch.float32, "h_out")))
 
     # ---- harness helpers
     def kv_write(self, B, layer, kv: KV, first_slot, n_slots, plain) -> None:

@@ -388,17 +388,23 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
     return HYDRA_OK;
 }
 
-// ---------------------------------------------------------------------------
-// verify
-// ---------------------------------------------------------------------------
-int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32_t *tree_tokens,
-                        const int32_t *seq_len, const hydra_kv *kv, float *hidden, int32_t *argmax, float *margin,
-                        float *logits) {
-    int rc = check_common(c, B, ws);
-    if (rc) return rc;
-    if (!tree_tokens || !seq_len || !hidden || !argmax) return fail(HYDRA_E_INVALID_ARG, "tree_verify_forward: NULL argument");
-    if ((rc = check_kv(c, kv))) return rc;
-    hipStream_t s = (hipStream_t)stream;
+}  // extern "C"
+
+namespace hydra {
+
+// Where the rows of a forward pass come from: token embeddings (tree_verify_forward) or given hidden states
+// gathered along an accepted path (hydra_prefix_attention).
+struct RowSource {
+    const int32_t *tokens;                       // [B, T] or NULL
+    const float *hidden; int T_src;              // [B, T_src, d] when tokens == NULL
+    const int32_t *path; const int32_t *n_acc;   // [B, T], [B]
+};
+
+// The decoder layers of the context over its B * T tree rows.  lm_tail: final RMSNorm, LM head, argmax (the
+// verify step); otherwise the residual stream after the last layer is left in the workspace's x.
+static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const RowSource &src, const int32_t *seq_len,
+                          const hydra_kv *kv, bool lm_tail, float *hidden, int32_t *argmax, float *margin, float *logits) {
+    int rc;
     const WsLayout w = ws_layout(c, B);
     char *W = (char *)ws, *A = c->arena;
     float *x = (float *)(W + w.x), *part = (float *)(W + w.part), *apart = (float *)(W + w.apart);
@@ -410,12 +416,14 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
     GemmPlan p;
     const RowScale none = {nullptr, 0, 0, 0, 0.f};
     if (c->bf16) {
-        // Fused flow.  The residual epilogues leave x, xg = bf16(x * gain of the next norm) and per-band sums of
+        // Fused flow.  The residual epilogues leave x, xg = half(x * gain of the next norm) and per-band sums of
         // squares; the 1/rms factor of each RMSNorm is applied by the consumer of the following GEMM.
         float *ss = (float *)(W + w.ss);
         const int Mpad = (int)align_up(std::max<size_t>(M, 1), 128);
         const RowScale rs = {ss, d / 32, Mpad, d, c->m.rms_eps};
-        if ((rc = launch_embed_prep(c, s, tree_tokens, x, (const float *)(A + c->layer[0].attn_norm), xa, ss, Mpad, M, flags))) return rc;
+        const float *gain0 = (const float *)(A + c->layer[0].attn_norm);
+        if (src.tokens) { if ((rc = launch_embed_prep(c, s, src.tokens, x, gain0, xa, ss, Mpad, M, flags))) return rc; }
+        else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, gain0, xa, ss, Mpad, flags))) return rc; }
         for (int l = 0; l < c->m.n_layers; ++l) {
             const LayerOff &o = c->layer[l];
             const float *next_gain = (const float *)(A + (l + 1 < c->m.n_layers ? c->layer[l + 1].attn_norm : c->off_final_norm));
@@ -425,12 +433,14 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
             if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, d / 32, Mpad, xb))) return rc;
             if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad, part))) return rc;
         }
+        if (!lm_tail) return HYDRA_OK;
         if ((rc = launch_final_hidden(c, s, x, (const float *)(A + c->off_final_norm), rs, hidden, M))) return rc;
         if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;
         if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rs, M, argmax, margin, logits))) return rc;
         return HYDRA_OK;
     }
-    if ((rc = launch_embed(c, s, tree_tokens, x, M, flags))) return rc;
+    if (src.tokens) { if ((rc = launch_embed(c, s, src.tokens, x, M, flags))) return rc; }
+    else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, nullptr, nullptr, nullptr, 0, flags))) return rc; }
     int S_prev = 0;                         // split-K partials of the previous residual branch, still to be added to x
     for (int l = 0; l < c->m.n_layers; ++l) {
         const LayerOff &o = c->layer[l];
@@ -445,10 +455,50 @@ int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32
         if ((rc = launch_gemm(c, s, xb, A + o.wdown, part, M, d, F, &p))) return rc;
         S_prev = p.splits;
     }
-    if ((rc = launch_rmsnorm(c, s, x, part, S_prev, ld_d, mp * ld_d, (const float *)(A + c->off_final_norm), xa, M, hidden))) return rc;
+    // adds the last residual branch to x; the normalised copy it also writes is what the LM head reads
+    if ((rc = launch_rmsnorm(c, s, x, part, S_prev, ld_d, mp * ld_d, (const float *)(A + c->off_final_norm), xa, M, lm_tail ? hidden : nullptr))) return rc;
+    if (!lm_tail) return HYDRA_OK;
     if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;
     if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, none, M, argmax, margin, logits))) return rc;
     return HYDRA_OK;
+}
+
+}  // namespace hydra
+
+extern "C" {
+
+// ---------------------------------------------------------------------------
+// verify
+// ---------------------------------------------------------------------------
+int tree_verify_forward(hydra_ctx *c, void *stream, int B, void *ws, const int32_t *tree_tokens,
+                        const int32_t *seq_len, const hydra_kv *kv, float *hidden, int32_t *argmax, float *margin,
+                        float *logits) {
+    int rc = check_common(c, B, ws);
+    if (rc) return rc;
+    if (!tree_tokens || !seq_len || !hidden || !argmax) return fail(HYDRA_E_INVALID_ARG, "tree_verify_forward: NULL argument");
+    if ((rc = check_kv(c, kv))) return rc;
+    const RowSource src = {tree_tokens, nullptr, 0, nullptr, nullptr};
+    return forward_layers(c, (hipStream_t)stream, B, ws, src, seq_len, kv, true, hidden, argmax, margin, logits);
+}
+
+// ---------------------------------------------------------------------------
+// Hydra++ prefix attention
+// ---------------------------------------------------------------------------
+int hydra_prefix_attention(hydra_ctx *c, void *stream, int B, void *ws, const float *hidden, int T_src,
+                           const int32_t *path, const int32_t *n_acc, int32_t *seq_len, const hydra_kv *kv,
+                           float *h_out) {
+    int rc = check_common(c, B, ws);
+    if (rc) return rc;
+    if (!hidden || !path || !n_acc || !seq_len || !h_out) return fail(HYDRA_E_INVALID_ARG, "hydra_prefix_attention: NULL argument");
+    if (T_src < 1) return fail(HYDRA_E_INVALID_ARG, "hydra_prefix_attention: T_src must be positive");
+    for (int n = 1; n < c->tree.T; ++n)
+        if (c->tree.parent[n] != n - 1) return fail(HYDRA_E_SHAPE, "hydra_prefix_attention: the context's tree must be a chain");
+    if ((rc = check_kv(c, kv))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    const RowSource src = {nullptr, hidden, T_src, path, n_acc};
+    if ((rc = forward_layers(c, s, B, ws, src, seq_len, kv, false, nullptr, nullptr, nullptr, nullptr))) return rc;
+    const WsLayout w = ws_layout(c, B);
+    return launch_prefix_select(c, s, B, (const float *)((char *)ws + w.x), n_acc, kv, seq_len, h_out);
 }
 
 int tree_attention(hydra_ctx *c, void *stream, int B, int layer, void *ws, const float *q, const int32_t *seq_len,

@@ -108,6 +108,6 @@ __device__ __forceinline__ float part_sum(const float *part, int S, size_t split
 
 __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
-enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2 };
+enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4 };
 
 }  // namespace hydra

@@ -387,4 +387,83 @@ int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_k
     return HYDRA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Prefix attention (paper, section 3.1 item 3): the extra decoder layer is fed
+// the base model's hidden states of the accepted tokens.  Row m = b*P + j of the
+// layer input is hidden[b, path[b][min(j, n_acc[b]-1)]]: positions past the
+// accepted length repeat the last accepted state (they sit after every valid
+// position in the chain, so nothing valid can see them).  Leaves x and, in the
+// 16-bit family, the GEMM input xg = half(x * gain) and the per-band sums of
+// squares, exactly as embed_prep_kernel does for token embeddings.
+// ---------------------------------------------------------------------------
+template <bool BF>
+__global__ __launch_bounds__(256) void gather_prep_kernel(const float *__restrict__ hidden, int T_src,
+                                                           const int32_t *__restrict__ path, const int32_t *__restrict__ n_acc,
+                                                           int P, float *__restrict__ x, const float *__restrict__ gain,
+                                                           a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad, int d,
+                                                           int32_t *flags) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    typedef __attribute__((ext_vector_type(4))) float f4;
+    const int m = blockIdx.x;
+    const int b = m / P, j = m - b * P;
+    int a = n_acc[b];
+    if (a < 1 || a > P) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_PATH);
+        a = a < 1 ? 1 : P;
+    }
+    int node = path[(size_t)b * P + (j < a ? j : a - 1)];
+    if (node < 0 || node >= T_src) {
+        if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_PATH);
+        node = 0;
+    }
+    const float *src = hidden + ((size_t)b * T_src + node) * d;
+    if (BF) {
+        for (int k = threadIdx.x * 8; k < d; k += 256 * 8) {          // d is a multiple of 128
+            const f4 v0 = *reinterpret_cast<const f4 *>(src + k), v1 = *reinterpret_cast<const f4 *>(src + k + 4);
+            const f4 g0 = *reinterpret_cast<const f4 *>(gain + k), g1 = *reinterpret_cast<const f4 *>(gain + k + 4);
+            *reinterpret_cast<f4 *>(x + (size_t)m * d + k) = v0;
+            *reinterpret_cast<f4 *>(x + (size_t)m * d + k + 4) = v1;
+            const u4 pk = {f2a_pack(v0[0] * g0[0], v0[1] * g0[1]), f2a_pack(v0[2] * g0[2], v0[3] * g0[3]),
+                           f2a_pack(v1[0] * g1[0], v1[1] * g1[1]), f2a_pack(v1[2] * g1[2], v1[3] * g1[3])};
+            *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
+            float sq = v0[0] * v0[0] + v0[1] * v0[1] + v0[2] * v0[2] + v0[3] * v0[3] + v1[0] * v1[0] + v1[1] * v1[1] + v1[2] * v1[2] + v1[3] * v1[3];
+            sq += __shfl_xor(sq, 1, 64); sq += __shfl_xor(sq, 2, 64);
+            if ((threadIdx.x & 3) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
+        }
+    } else {
+        for (int k = threadIdx.x; k < d; k += 256) x[(size_t)m * d + k] = src[k];
+    }
+}
+
+int launch_gather_prep(hydra_ctx *c, hipStream_t s, int B, const float *hidden, int T_src, const int32_t *path,
+                       const int32_t *n_acc, float *x, const float *gain, void *xg, float *ss, int Mpad, int32_t *flags) {
+    const int P = c->tree.T;
+    if (c->bf16) hipLaunchKernelGGL(gather_prep_kernel<true>, dim3(B * P), dim3(256), 0, s, hidden, T_src, path, n_acc, P, x, gain, (a16_t *)xg, ss, Mpad, c->m.d, flags);
+    else         hipLaunchKernelGGL(gather_prep_kernel<false>, dim3(B * P), dim3(256), 0, s, hidden, T_src, path, n_acc, P, x, gain, (a16_t *)xg, ss, Mpad, c->m.d, flags);
+    HYDRA_LAUNCH_CHECK("gather_prep_kernel");
+    return HYDRA_OK;
+}
+
+// h_out[b] = layer output at the last accepted position; seq_len[b] += n_acc[b].  Rows the layer kernels
+// skipped for lack of cache capacity are left as they are.
+__global__ __launch_bounds__(256) void prefix_select_kernel(const float *__restrict__ x, const int32_t *__restrict__ n_acc, int P,
+                                                             int max_pages, int d, int32_t *seq_len, float *__restrict__ h_out) {
+    const int b = blockIdx.x;
+    const int L = seq_len[b];
+    if (L < 0 || L + P > max_pages * 16) return;
+    int a = n_acc[b];
+    a = a < 1 ? 1 : (a > P ? P : a);
+    const float *src = x + ((size_t)b * P + a - 1) * d;
+    for (int k = threadIdx.x; k < d; k += 256) h_out[(size_t)b * d + k] = src[k];
+    __syncthreads();                                        // every thread has read seq_len[b]
+    if (threadIdx.x == 0) seq_len[b] = L + a;
+}
+
+int launch_prefix_select(hydra_ctx *c, hipStream_t s, int B, const float *x, const int32_t *n_acc, const hydra_kv *kv,
+                         int32_t *seq_len, float *h_out) {
+    hipLaunchKernelGGL(prefix_select_kernel, dim3(B), dim3(256), 0, s, x, n_acc, c->tree.T, kv->max_pages, c->m.d, seq_len, h_out);
+    HYDRA_LAUNCH_CHECK("prefix_select_kernel");
+    return HYDRA_OK;
+}
+
 }  // namespace hydra

@@ -133,6 +133,10 @@ int launch_copy_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, 
 int launch_to_f32(hydra_ctx *c, hipStream_t s, const void *src, float *dst, int n);
 
 // glue
+int launch_gather_prep(hydra_ctx *c, hipStream_t s, int B, const float *hidden, int T_src, const int32_t *path,
+                       const int32_t *n_acc, float *x, const float *gain, void *xg, float *ss, int Mpad, int32_t *flags);
+int launch_prefix_select(hydra_ctx *c, hipStream_t s, int B, const float *x, const int32_t *n_acc, const hydra_kv *kv,
+                         int32_t *seq_len, float *h_out);
 struct VerifyArgs;
 int launch_embed(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, int M, int32_t *flags);
 int launch_rmsnorm(hydra_ctx *c, hipStream_t s, float *x, const float *part, int S, int part_ld, size_t part_split_stride,

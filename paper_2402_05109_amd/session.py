@@ -85,6 +85,25 @@ class Session:
         self._growth_since_copy = 0
         self._steps_since_copy = 0
         self.ws = torch.empty(max(self.main.workspace_bytes(B), 256), dtype=torch.uint8, device=self.dev)
+        # Hydra++ prefix attention: a one-layer context family of its own (weights, cache, length); it shares the
+        # page table with the base cache (same slots, its own page storage)
+        self.prefix = bool(getattr(shape, "prefix", 0))
+        self._pctx: Dict[int, hb.Hydra] = {}
+        if self.prefix:
+            self._pnext_slot = 0
+            first = self._prefix_ctx_new(self.main.depth + 1)
+            self.parena = torch.empty(first.weights_bytes(), dtype=torch.uint8, device=self.dev)
+            self._prefix_bind(first)
+            for nm, kind in (("attn_norm", hb.W_ATTN_NORM), ("wq", hb.W_WQ), ("wk", hb.W_WK), ("wv", hb.W_WV), ("wo", hb.W_WO),
+                             ("ffn_norm", hb.W_FFN_NORM), ("w_gate", hb.W_GATE), ("w_up", hb.W_UP), ("w_down", hb.W_DOWN)):
+                first.load_tensor(kind, 0, 0, get_tensor(f"prefix.{nm}"))
+            first.load_tensor(hb.W_FINAL_NORM, 0, 0, torch.ones(shape.d, dtype=self.tdtype, device=self.dev))   # never used; kept defined
+            torch.cuda.synchronize()
+            n_el1 = self.n_pages * shape.H * 16 * shape.Dh
+            self.pk_pages = torch.zeros(n_el1, dtype=cache_dtype, device=self.dev)
+            self.pv_pages = torch.zeros(n_el1, dtype=cache_dtype, device=self.dev)
+            self.pkv = hb.KV(self.pk_pages, self.pv_pages, self.page_table, self.n_pages, seq_len_hint=0)
+            self.pseq_len = torch.zeros(B, dtype=torch.int32, device=self.dev)
 
     # ---- contexts -----------------------------------------------------------
     def _make_ctx(self, name: str, parent: Sequence[int]) -> hb.Hydra:
@@ -112,6 +131,35 @@ class Session:
                 torch.cuda.synchronize()
                 self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
         return self._ctx[name]
+
+    # ---- prefix-attention contexts (one per chain length) --------------------------
+    def _prefix_ctx_new(self, P: int) -> hb.Hydra:
+        s = self.shape
+        c = hb.Hydra(d=s.d, n_layers=1, n_heads=s.H, head_dim=s.Dh, ffn=s.F, vocab=32, dtype=self.dtype_code,
+                     rms_eps=s.rms_eps, rope_theta=s.rope_theta, max_pos=self._max_pos, n_draft_heads=0,
+                     mlp_layers=1, include_root_embedding=1, parent=chain_parent(P), max_batch=self.B)
+        self._pctx[P] = c
+        return c
+
+    def _prefix_bind(self, c: hb.Hydra) -> None:
+        c.bind_weights(self.parena, self._pnext_slot)
+        self._pnext_slot += 1
+        need = c.workspace_bytes(self.B)
+        if need > self.ws.numel():
+            torch.cuda.synchronize()
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+
+    def prefix_ctx(self, P: int) -> hb.Hydra:
+        if P not in self._pctx:
+            self._prefix_bind(self._prefix_ctx_new(P))
+        return self._pctx[P]
+
+    def prefix_attention(self, name: str = "main") -> None:
+        """Feeds the accepted tokens' hidden states of context `name` to the prefix layer; h_last becomes its output."""
+        c, o = self._ctx[name], self._out[name]
+        P = o.path.shape[1]
+        self.pkv.seq_len_hint = self.host_len
+        self.prefix_ctx(P).hydra_prefix_attention(self.B, self.ws, o.hidden, c.T, o.path, o.n_acc, self.pseq_len, self.pkv, self.h_last)
 
     def out(self, name: str = "main") -> _Outputs:
         return self._out[name]
@@ -142,6 +190,8 @@ class Session:
 
     def reset(self) -> None:
         self.seq_len.zero_(); self.h_last.zero_(); self.root.zero_()
+        if self.prefix:
+            self.pseq_len.zero_()
         self.host_len = 0
         self._len_event = None
 
@@ -167,6 +217,8 @@ class Session:
             o.next_root.copy_(o.argmax[:, n - 1])
             c.kv_compact(B, o.n_acc, o.path, o.next_root, o.last_node, o.hidden, self.kv, self.seq_len, self.h_last,
                          self.root, o.kv_index)
+            if self.prefix:
+                self.prefix_attention(name)           # hint: still the length before this chunk
             pos += n
             self.host_len += n
 
@@ -200,7 +252,12 @@ class Session:
             hook(self._out[name])
         self.verify(name)
         self.accept(name)
+        pre = self.host_len
         self.compact(name)
+        if self.prefix:
+            post, self.host_len = self.host_len, pre          # the prefix cache is as long as the base cache was before compaction
+            self.prefix_attention(name)
+            self.host_len = post
 
     def _refresh_bound(self, every: int = 8) -> None:
         """Asynchronous tightening of the host bound on seq_len: no synchronisation, the value is used when it has arrived."""

@@ -42,9 +42,9 @@ _BASE_SEED = 0x5EED0000
 CONFIGS = {
     1: ModelShape("tiny", 256, 2, 4, 64, 688, 1024, "f32", 3, 1, 16, (1,), (128,), 64, _BASE_SEED + 1),
     2: ModelShape("7b", 4096, 32, 32, 128, 11008, 32000, "bf16", 4, 1, 64, (1,), (512,), 256, _BASE_SEED + 2),
-    3: ModelShape("7b++", 4096, 32, 32, 128, 11008, 32000, "bf16", 4, 4, 64, (1, 4, 8, 16), (1024,), 256, _BASE_SEED + 3),
-    4: ModelShape("13b", 5120, 40, 40, 128, 13824, 32000, "bf16", 4, 4, 64, (1,), (512, 2048, 4096), 256, _BASE_SEED + 4),
-    5: ModelShape("33b", 6656, 60, 52, 128, 17920, 32000, "bf16", 4, 4, 64, (1, 4), (2048,), 256, _BASE_SEED + 5),
+    3: ModelShape("7b++", 4096, 32, 32, 128, 11008, 32000, "bf16", 4, 4, 64, (1, 4, 8, 16), (1024,), 256, _BASE_SEED + 3, prefix=1),
+    4: ModelShape("13b", 5120, 40, 40, 128, 13824, 32000, "bf16", 4, 4, 64, (1,), (512, 2048, 4096), 256, _BASE_SEED + 4, prefix=1),
+    5: ModelShape("33b", 6656, 60, 52, 128, 17920, 32000, "bf16", 4, 4, 64, (1, 4), (2048,), 256, _BASE_SEED + 5, prefix=1),
 }
 
 

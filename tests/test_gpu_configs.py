@@ -113,6 +113,46 @@ def test_draft_and_verify_at_full_width(idx, over, B, lens):
             kv = to_np(t[b])
             worst["k"] = max(worst["k"], max_rel(kv[:, 0].reshape(T, -1), caches[b].K[l, L:L + T].reshape(T, -1)))
             worst["v"] = max(worst["v"], max_rel(kv[:, 1].reshape(T, -1), caches[b].V[l, L:L + T].reshape(T, -1)))
+    # ---- Hydra++ prefix attention on a scripted accepted path (left-most chain, length varying with the row)
+    rngp = np.random.default_rng(200 + idx)
+    pcs = []
+    pctx = sess.prefix_ctx(tree.max_depth + 1)
+    plain = np.zeros((B, Lmax, 2, cfg.H, cfg.Dh))
+    for b in range(B):
+        pc = O.PrefixCache(m, Lmax + T)
+        pc.K[:lens[b]] = h16(rngp.standard_normal(pc.K[:lens[b]].shape) * 0.5)
+        pc.V[:lens[b]] = h16(rngp.standard_normal(pc.V[:lens[b]].shape) * 0.5)
+        plain[b, :, 0], plain[b, :, 1] = pc.K[:Lmax], pc.V[:Lmax]
+        pcs.append(pc)
+    pctx.kv_write(B, 0, sess.pkv, 0, Lmax, torch.tensor(plain, dtype=torch.float32, device=dev).contiguous())
+    sess.pseq_len.copy_(torch.tensor(lens, dtype=torch.int32))
+    chain = [0]
+    while tree.children[chain[-1]]:
+        chain.append(tree.children[chain[-1]][0])
+    n_accs = [1 + (b + idx) % len(chain) for b in range(B)]
+    path = np.full((B, tree.max_depth + 1), -1, dtype=np.int32)
+    for b in range(B):
+        path[b, :n_accs[b]] = chain[:n_accs[b]]
+    o.path.copy_(torch.tensor(path)); o.n_acc.copy_(torch.tensor(n_accs, dtype=torch.int32))
+    hid_gpu = to_np(o.hidden)                           # the layer's input is the library's own verify output
+    sess.host_len = Lmax
+    sess.prefix_attention()
+    torch.cuda.synchronize()
+    assert pctx.read_flags() == 0
+    assert sess.pseq_len.tolist() == [lens[b] + n_accs[b] for b in range(B)]
+    worst_p = 0.0
+    for b in range(B):
+        for j in range(n_accs[b]):
+            g = O.prefix_token(m, pcs[b], hid_gpu[b, chain[j]], lens[b] + j)
+        worst_p = max(worst_p, max_rel(to_np(sess.h_last[b]), g))
+        t = torch.zeros(B, n_accs[b], 2, cfg.H, cfg.Dh, dtype=torch.float32, device=dev)
+        pctx.kv_read(B, 0, sess.pkv, lens[b], n_accs[b], t)
+        kvp = to_np(t[b])
+        worst_p = max(worst_p, max_rel(kvp[:, 0].reshape(n_accs[b], -1), pcs[b].K[lens[b]:lens[b] + n_accs[b]].reshape(n_accs[b], -1)))
+        worst_p = max(worst_p, max_rel(kvp[:, 1].reshape(n_accs[b], -1), pcs[b].V[lens[b]:lens[b] + n_accs[b]].reshape(n_accs[b], -1)))
+    print(f"config {idx}: prefix attention, accepted lengths {n_accs}: worst error {worst_p:.4f}", flush=True)
+    assert worst_p <= TOL
+
     print(f"config {idx} {over} B={B}: draft {exact} nodes exact / {audited} audited; verify hidden {worst['h']:.4f} "
           f"logits {worst['l']:.4f} K {worst['k']:.4f} V {worst['v']:.4f}; {skipped} near-tie rows of {B * T}", flush=True)
     assert max(worst.values()) <= TOL
