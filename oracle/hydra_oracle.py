@@ -384,6 +384,62 @@ def kv_compact(cache, L, path):
 
 
 # ----------------------------------------------------------------------------
+# Typical acceptance (paper, section 6.3): a candidate token x^ at node c, child
+# of node p, passes if   p_base(x^ | path to p; tau) > min(eps, alpha * exp(-H))
+# with p_base(. ; tau) = softmax(logits[p] / tau) and H its entropy (natural log).
+#
+# Readings (the paper gives the per-token test only): the accepted continuation is
+# the deepest node all of whose path tokens pass, the lowest node id among equally
+# deep ones; the root x_t always counts; the next root is drawn from
+# p_base(. | accepted path; tau) by inverting its cumulative distribution in token
+# id order at a uniform number u in [0, 1) supplied by the caller (u = None: the
+# most likely token, lowest id at ties).
+# ----------------------------------------------------------------------------
+def tempered_probs(logits_row, tau):
+    z = np.asarray(logits_row, dtype=np.float64) / tau
+    return softmax(z)
+
+
+def entropy(p):
+    p = np.asarray(p, dtype=np.float64)
+    nz = p > 0
+    return float(-np.sum(p[nz] * np.log(p[nz])))
+
+
+def typical_pass(logits_row, token, tau, eps, alpha):
+    """The per-token test of section 6.3 for a child carrying `token` under a node whose logits are given."""
+    p = tempered_probs(logits_row, tau)
+    return bool(p[int(token)] > min(eps, alpha * np.exp(-entropy(p))))
+
+
+def sample_inverse_cdf(p, u):
+    """Smallest id v with p[0] + ... + p[v] > u * sum(p)."""
+    c = np.cumsum(np.asarray(p, dtype=np.float64))
+    v = int(np.searchsorted(c, u * c[-1], side="right"))
+    return min(v, len(c) - 1)
+
+
+def accept_typical(tree, tok, logits, tau, eps, alpha, u=None):
+    """Returns (n_acc, path, next_root, last_node) under the typical-acceptance criterion."""
+    ok = [True] * tree.T
+    for c in range(1, tree.T):
+        ok[c] = typical_pass(logits[tree.parent[c]], tok[c], tau, eps, alpha)
+    best = 0
+    reach = [False] * tree.T
+    reach[0] = True
+    for c in range(1, tree.T):                                   # parents come before children
+        reach[c] = reach[tree.parent[c]] and ok[c]
+        if reach[c] and tree.depth[c] > tree.depth[best]:
+            best = c                                             # first (lowest id) node of a new depth
+    path = tree.path(best)
+    if u is None:
+        nxt = argmax_lowest(logits[best])
+    else:
+        nxt = sample_inverse_cdf(tempered_probs(logits[best], tau), u)
+    return len(path), list(path), int(nxt), best
+
+
+# ----------------------------------------------------------------------------
 # Hydra++ prefix attention (paper, section 3.1 item 3; appendix, "Hydra-specific
 # prefix attention"): one more decoder layer on top of the base model whose only
 # role is to produce the hidden state the draft heads read.  It runs over the
