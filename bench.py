@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--tree", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="candidate-tree size (nodes with the root); 0 = the configuration's own (the headline workload)")
+    ap.add_argument("--typical", action="store_true",
+                    help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
     args = ap.parse_args()
@@ -125,7 +127,8 @@ def main():
     spec = WeightSpec(cfg)
     dev = "cuda:0"
     max_len = L0 + (args.steps + args.warmup + 8 + 3 * 40) * (cfg.K + 1) + 2 * cfg.T
-    sess = Session(cfg, parent, B, max_len, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=128)
+    sess = Session(cfg, parent, B, max_len, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=128,
+                   want_logits=args.typical)
     prompts = torch.stack([uniform_tokens(cfg.seed, b, L0, cfg.V) for b in range(B)])
     sess.prefill(prompts)
     torch.cuda.synchronize()
@@ -170,6 +173,10 @@ def main():
     t_verify = timed(sess.verify)
     t_tail = timed(lambda: (sess.accept(), sess.compact()))
     t_prefix = timed(sess.prefix_attention) if sess.prefix else None
+    t_typical = None
+    if args.typical:
+        u_dev = torch.rand(B, device=dev)
+        t_typical = timed(lambda: sess.accept_typical(0.7, 0.15, 0.15 ** 0.5, u_dev))
     vb = verify_bytes(cfg, B, L_end, cfg.T)
 
     # dominant kernel: the weight-streaming GEMM.  HIP events (recorded by the library on the launch stream)
@@ -248,6 +255,7 @@ def main():
         "draft": {"ms": t_draft, "algorithmic_GB": draft_bytes(cfg) / 1e9, "GBps": draft_bytes(cfg) / (t_draft * 1e-3) / 1e9},
         "accept_compact_ms": t_tail,
         "prefix_attention_ms": t_prefix,
+        "accept_typical_ms": t_typical,
         "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
         "injected_acceptance": injected,
         "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",

@@ -223,6 +223,23 @@ int accept_greedy(hydra_ctx *ctx, void *stream, int B,
                   const int32_t *tree_tokens, const int32_t *argmax,
                   int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
 
+/* Section 6.3, typical acceptance: the token of child c of node n passes if
+ *   p(tree_tokens[c]) > min(eps, alpha * exp(-H(p))),  p = softmax(logits[n] / tau),
+ * H the entropy in nats.  The accepted path ends at the deepest node all of
+ * whose path tokens pass (lowest node id among equally deep ones); the root
+ * always counts.  next_root = the most likely token at that node (u == NULL,
+ * lowest id at ties) or, with u[b] in [0, 1), the token at which the cumulative
+ * distribution of softmax(logits[last] / tau), taken in token-id order, first
+ * exceeds u[b].  The per-token test is the paper's; path selection and the
+ * draw of the next root are this library's reading (the paper states neither).
+ *   logits device [B, T, V] fp32: tree_verify_forward's optional output
+ *   u      device [B] fp32 or NULL           other outputs as in accept_greedy.
+ * Probabilities are computed in fp32.  Requires tau > 0, eps >= 0, alpha >= 0. */
+int accept_typical(hydra_ctx *ctx, void *stream, int B, void *ws,
+                   const int32_t *tree_tokens, const float *logits,
+                   float tau, float eps, float alpha, const float *u,
+                   int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
+
 /* Keeps the accepted tokens.  Per row, every layer, j = 0..n_acc-1: K/V slot
  * seq_len + path[j] -> slot seq_len + j (in place; sources are read before any
  * destination is written).  Then h_last[b] = hidden[b, last_node[b]],

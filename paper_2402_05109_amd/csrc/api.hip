@@ -529,6 +529,20 @@ int accept_greedy(hydra_ctx *c, void *stream, int B, const int32_t *tree_tokens,
     return launch_accept(c, (hipStream_t)stream, B, tree_tokens, argmax, n_acc, path, next_root, last_node);
 }
 
+int accept_typical(hydra_ctx *c, void *stream, int B, void *ws, const int32_t *tree_tokens, const float *logits,
+                   float tau, float eps, float alpha, const float *u, int32_t *n_acc, int32_t *path,
+                   int32_t *next_root, int32_t *last_node) {
+    int rc = check_common(c, B, ws);
+    if (rc) return rc;
+    if (!tree_tokens || !logits || !n_acc || !path || !next_root || !last_node)
+        return fail(HYDRA_E_INVALID_ARG, "accept_typical: NULL argument");
+    if (!(tau > 0.f) || !(eps >= 0.f) || !(alpha >= 0.f)) return fail(HYDRA_E_INVALID_ARG, "accept_typical: need tau > 0, eps >= 0, alpha >= 0");
+    const WsLayout w = ws_layout(c, B);
+    int32_t *ok = (int32_t *)((char *)ws + w.part);          // B * T flags; the GEMM partial buffer is free between calls
+    return launch_accept_typical(c, (hipStream_t)stream, B, tree_tokens, logits, tau, eps, alpha, u, ok, flags_ptr(c), n_acc, path,
+                                 next_root, last_node);
+}
+
 int kv_compact(hydra_ctx *c, void *stream, int B, const int32_t *n_acc, const int32_t *path,
                const int32_t *next_root, const int32_t *last_node, const float *hidden, const hydra_kv *kv,
                int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index) {

@@ -253,6 +253,159 @@ int launch_accept(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens
 }
 
 // ---------------------------------------------------------------------------
+// Typical acceptance (paper, section 6.3): the child c of node n passes if
+//   p(tok[c]) > min(eps, alpha * exp(-H)),  p = softmax(logits[n] / tau), H = entropy(p).
+// Kernel 1, one workgroup per (row, node with children): max, Z = sum exp(z - max),
+// S = sum exp(z - max) (z - max) with z = logit / tau, so H = ln Z - S / Z; then the
+// test for each child.  Kernel 2, one workgroup per row: the deepest node whose whole
+// path passes (lowest id among equally deep ones), and the next root: the most likely
+// token of that node, or the token at which the cumulative distribution of
+// softmax(logits / tau), taken in id order, first exceeds u.
+// ---------------------------------------------------------------------------
+enum { TYP_THREADS = 1024 };
+
+__device__ __forceinline__ float block_reduce(float v, float *sh, bool is_max) {
+    v = is_max ? wave_max(v) : wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = sh[0];
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];   // fixed order
+    return r;
+}
+
+__global__ __launch_bounds__(TYP_THREADS) void typical_stats_kernel(const float *__restrict__ logits, int V,
+                                                                     const TreeDev *tree, const int32_t *__restrict__ tree_tokens,
+                                                                     float inv_tau, float eps, float alpha,
+                                                                     int32_t *__restrict__ ok, int32_t *flags) {
+    __shared__ float sh[16];
+    const int n = blockIdx.x, b = blockIdx.y, T = tree->T;
+    const int nc = tree->n_children[n];
+    if (nc == 0) return;                                            // uniform over the workgroup
+    const float *row = logits + ((size_t)b * T + n) * V;
+    float m = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += TYP_THREADS) m = fmaxf(m, row[v]);
+    m = block_reduce(m, sh, true);
+    float z = 0.f, sz = 0.f;
+    for (int v = threadIdx.x; v < V; v += TYP_THREADS) {
+        const float t = (row[v] - m) * inv_tau;                     // <= 0
+        const float e = __expf(t);
+        z += e;
+        sz += e > 0.f ? e * t : 0.f;                                // exp underflow: 0 * (-inf) must not appear
+    }
+    z = block_reduce(z, sh, false);
+    sz = block_reduce(sz, sh, false);
+    const float H = __logf(z) - sz / z;
+    const float th = fminf(eps, alpha * __expf(-H));
+    const int first = tree->first_child[n];
+    for (int i = threadIdx.x; i < nc; i += TYP_THREADS) {
+        const int c = first + i;
+        int tok = tree_tokens[(size_t)b * T + c];
+        if (tok < 0 || tok >= V) { atomicOr(flags, FLAG_BAD_TOKEN); tok = 0; }
+        const float p = __expf((row[tok] - m) * inv_tau) / z;
+        ok[(size_t)b * T + c] = p > th ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(TYP_THREADS) void typical_select_kernel(const float *__restrict__ logits, int V, const TreeDev *tree,
+                                                                      const int32_t *__restrict__ ok, float inv_tau,
+                                                                      const float *__restrict__ u, int32_t *n_acc,
+                                                                      int32_t *path, int32_t *next_root, int32_t *last_node) {
+    __shared__ float sh[16];
+    __shared__ float wsum[16];
+    __shared__ int best_s;
+    __shared__ int cand[16];
+    const int b = blockIdx.x, T = tree->T, plen = tree->max_depth + 1;
+    if (threadIdx.x == 0) {
+        // nodes are in breadth-first order: parents first, depth non-decreasing
+        uint64_t reach[2] = {1ull, 0ull};
+        int best = 0;
+        for (int c = 1; c < T; ++c) {
+            const int pa = tree->parent[c];
+            if (((reach[pa >> 6] >> (pa & 63)) & 1ull) && ok[(size_t)b * T + c]) {
+                reach[c >> 6] |= 1ull << (c & 63);
+                if (tree->depth[c] > tree->depth[best]) best = c;
+            }
+        }
+        best_s = best;
+        const int len = tree->depth[best] + 1;
+        int32_t *p = path + (size_t)b * plen;
+        int cur = best;
+        for (int j = len - 1; j >= 0; --j) { p[j] = cur; cur = tree->parent[cur]; }
+        for (int j = len; j < plen; ++j) p[j] = -1;
+        n_acc[b] = len;
+        last_node[b] = best;
+    }
+    __syncthreads();
+    const int best = best_s;
+    const float *row = logits + ((size_t)b * T + best) * V;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (!u) {
+        // most likely token, lowest id at ties
+        float bv = -INFINITY; int bi = 0x7fffffff;
+        for (int v = threadIdx.x; v < V; v += TYP_THREADS) {
+            const float x = row[v];
+            if (x > bv) { bv = x; bi = v; }                         // ascending v per thread: first maximum kept
+        }
+        Cand cnd = wave_best(Cand{bv, bi});
+        __shared__ Cand red[16];
+        if (lane == 0) red[wave] = cnd;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            Cand w = red[0];
+            for (int i = 1; i < 16; ++i) if (better(red[i].v, red[i].id, w.v, w.id)) w = red[i];
+            next_root[b] = w.id;
+        }
+        return;
+    }
+    float m = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += TYP_THREADS) m = fmaxf(m, row[v]);
+    m = block_reduce(m, sh, true);
+    // thread t owns the contiguous ids [t*C, (t+1)*C): local mass, then an exclusive scan over threads in id order
+    const int C = (V + TYP_THREADS - 1) / TYP_THREADS;
+    const int v0 = threadIdx.x * C, v1 = min(V, v0 + C);
+    float local = 0.f;
+    for (int v = v0; v < v1; ++v) local += __expf((row[v] - m) * inv_tau);
+    float incl = local;                                             // inclusive scan inside the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    float before = 0.f, total = 0.f;
+    for (int w = 0; w < 16; ++w) { if (w < wave) before += wsum[w]; total += wsum[w]; }
+    const float excl = before + incl - local;
+    const float target = u[b] * total;
+    if (threadIdx.x < 16) cand[threadIdx.x] = 0x7fffffff;
+    __syncthreads();
+    // the first id whose cumulative mass exceeds the target lies in the first thread range with excl + local > target
+    if (local > 0.f && excl + local > target && excl <= target) {
+        float c = excl; int pick = v1 - 1;
+        for (int v = v0; v < v1; ++v) {
+            c += __expf((row[v] - m) * inv_tau);
+            if (c > target) { pick = v; break; }
+        }
+        atomicMin(&cand[0], pick);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) next_root[b] = cand[0] == 0x7fffffff ? V - 1 : cand[0];
+}
+
+int launch_accept_typical(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens, const float *logits, float tau,
+                          float eps, float alpha, const float *u, int32_t *ok_scratch, int32_t *flags, int32_t *n_acc,
+                          int32_t *path, int32_t *next_root, int32_t *last_node) {
+    const int T = c->tree.T, V = c->m.vocab;
+    hipLaunchKernelGGL(typical_stats_kernel, dim3(T, B), dim3(TYP_THREADS), 0, s, logits, V, tree_dev(c), tree_tokens, 1.0f / tau, eps, alpha, ok_scratch, flags);
+    HYDRA_LAUNCH_CHECK("typical_stats_kernel");
+    hipLaunchKernelGGL(typical_select_kernel, dim3(B), dim3(TYP_THREADS), 0, s, logits, V, tree_dev(c), ok_scratch, 1.0f / tau, u, n_acc, path, next_root, last_node);
+    HYDRA_LAUNCH_CHECK("typical_select_kernel");
+    return HYDRA_OK;
+}
+
+// ---------------------------------------------------------------------------
 // Cache compaction: slot L + path[j] -> slot L + j for j < n_acc, every layer.
 // A thread owns one (layer, head, dim) element column and walks j upwards;
 // path[j] >= j and strictly increasing, so within a column every source is read

@@ -235,6 +235,13 @@ class Session:
         c, o = self.ctx(name), self._out[name]
         c.accept_greedy(self.B, o.tree_tokens, o.argmax, o.n_acc, o.path, o.next_root, o.last_node)
 
+    def accept_typical(self, tau: float, eps: float, alpha: float, u: Optional[torch.Tensor] = None, name: str = "main") -> None:
+        """Typical acceptance instead of greedy acceptance; needs the session to keep logits (want_logits=True)."""
+        c, o = self.ctx(name), self._out[name]
+        if o.logits is None:
+            raise ValueError("typical acceptance needs the logits: create the Session with want_logits=True")
+        c.accept_typical(self.B, self.ws, o.tree_tokens, o.logits, tau, eps, alpha, u, o.n_acc, o.path, o.next_root, o.last_node)
+
     def compact(self, name: str = "main") -> None:
         c, o = self.ctx(name), self._out[name]
         self._hint(c.T)
