@@ -130,11 +130,12 @@ class Model:
 
     def __init__(self, d, NL, H, Dh, F, V, K, mlp_layers, weights,
                  rms_eps=1e-6, rope_theta=10000.0, include_root_embedding=1,
-                 keep_converted=False):
+                 keep_converted=False, medusa=0):
         self.d, self.NL, self.H, self.Dh, self.F, self.V = d, NL, H, Dh, F, V
         self.K, self.mlp_layers = K, mlp_layers
         self.eps, self.theta = rms_eps, rope_theta
         self.include_root_embedding = include_root_embedding
+        self.medusa = medusa                          # 1: sequentially independent draft heads (paper, section 2)
         self.weights = weights
         self._kept = {} if keep_converted else None   # small models: convert once
         assert H * Dh == d
@@ -234,8 +235,19 @@ def head_logits(model, i, h_last, path_tokens):
     for Hydra++ (section 3.1, "Scaling") layers 2..n are z + SiLU(W z + b);
     a per-head vocabulary projection Wout without bias.  With
     include_root_embedding = 0 the embedding of x_t is left out of u.
+
+    model.medusa (paper, section 2, "Lightweight heads as a draft model" and "Medusa
+    decoding"): the head sees h_{t-1} only, p_draft = f_draft,i(h_{t-1}), and its
+    first layer is a single-layer MLP with a residual connection,
+    z = h + SiLU(W1 h + b1) with W1 [d, d]; the path tokens are ignored.
     """
     m = model
+    if m.medusa:
+        h = np.asarray(h_last, dtype=np.float64)
+        z = h + silu(m.w(f"heads.{i}.w1") @ h + m.w(f"heads.{i}.b1"))
+        for j in range(2, m.mlp_layers + 1):
+            z = z + silu(m.w(f"heads.{i}.w{j}") @ z + m.w(f"heads.{i}.b{j}"))
+        return m.w(f"heads.{i}.wout") @ z
     E = m.w("embed")
     toks = list(path_tokens)
     assert len(toks) == i

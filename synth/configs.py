@@ -31,6 +31,7 @@ class ModelShape:
     rope_theta: float = 10000.0
     page: int = 16
     include_root_embedding: int = 1
+    medusa: int = 0       # 1: sequentially independent heads on h_last only, first MLP layer residual (the baseline draft head)
     prefix: int = 0       # 1: Hydra++ prefix-attention layer (one extra decoder layer feeding the draft heads)
 
     def with_(self, **kw) -> "ModelShape":

@@ -9,7 +9,7 @@ Tensor names and shapes (row-major, [out_features, in_features]):
     embed [V,d]  lm_head [V,d]  final_norm [d]
     layers.L.attn_norm [d]  layers.L.wq|wk|wv|wo [d,d]
     layers.L.ffn_norm [d]   layers.L.w_gate|w_up [F,d]  layers.L.w_down [d,F]
-    heads.I.w1 [d,(I+1)d]  (or [d, I*d] without the root embedding), heads.I.b1 [d]
+    heads.I.w1 [d,(I+1)d]  (or [d, I*d] without the root embedding; [d, d] for Medusa-style heads), heads.I.b1 [d]
     heads.I.wJ [d,d], heads.I.bJ [d]  for J = 2..mlp_layers
     heads.I.wout [V,d]                                   I = 1..K
     prefix.<same nine names as a decoder layer>          when the configuration has the prefix-attention layer
@@ -32,6 +32,8 @@ class WeightSpec:
 
     def head_in_width(self, i: int) -> int:
         c = self.shape_cfg
+        if c.medusa:
+            return c.d
         return (i + 1) * c.d if c.include_root_embedding else i * c.d
 
 

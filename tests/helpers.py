@@ -22,4 +22,4 @@ def make_weights(cfg: ModelShape, gain_std=0.1, std=0.02, device="cpu") -> dict:
 def oracle_model(cfg: ModelShape, weights: dict, keep=True) -> O.Model:
     return O.Model(cfg.d, cfg.NL, cfg.H, cfg.Dh, cfg.F, cfg.V, cfg.K, cfg.mlp_layers, weights,
                    rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta,
-                   include_root_embedding=cfg.include_root_embedding, keep_converted=keep)
+                   include_root_embedding=cfg.include_root_embedding, keep_converted=keep, medusa=cfg.medusa)
