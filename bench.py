@@ -43,7 +43,8 @@ def draft_bytes(cfg):
     e = 2 if cfg.dtype == "bf16" else 4
     tot = 0
     for i in range(1, cfg.K + 1):
-        tot += e * ((i + 1) * cfg.d * cfg.d + (cfg.mlp_layers - 1) * cfg.d * cfg.d + cfg.d * cfg.V)
+        w1_in = 1 if cfg.medusa else (i + 1 if cfg.include_root_embedding else i)
+        tot += e * (w1_in * cfg.d * cfg.d + (cfg.mlp_layers - 1) * cfg.d * cfg.d + cfg.d * cfg.V)
     return tot
 
 
@@ -103,6 +104,8 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--tree", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="candidate-tree size (nodes with the root); 0 = the configuration's own (the headline workload)")
+    ap.add_argument("--medusa", action="store_true",
+                    help="Medusa-style draft heads (h_last only, residual single-layer MLP) instead of Hydra heads: the baseline draft cost")
     ap.add_argument("--typical", action="store_true",
                     help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -121,6 +124,8 @@ def main():
         cfg = cfg.with_(NL=args.layers)
     if args.tree:
         cfg = cfg.with_(T=args.tree)
+    if args.medusa:
+        cfg = cfg.with_(medusa=1)
     tree_name = {16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T]
     parent = frozen_tree(tree_name)
     B, L0 = cfg.batch[0], cfg.prompt[0]
@@ -246,7 +251,7 @@ def main():
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights, f16 activations and KV cache, f32 accumulation" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg.name} shape d={cfg.d} NL={cfg.NL} H={cfg.H}x{cfg.Dh} F={cfg.F} V={cfg.V}, "
-                               f"{cfg.K} Hydra heads x {cfg.mlp_layers}-layer MLP{' + prefix-attention layer' if cfg.prefix else ''}, tree {tree_name} (T={cfg.T}), B={B}, "
+                               f"{cfg.K} {'Medusa-style' if cfg.medusa else 'Hydra'} heads x {cfg.mlp_layers}-layer MLP{' + prefix-attention layer' if cfg.prefix else ''}, tree {tree_name} (T={cfg.T}), B={B}, "
                                f"prompt {L0} uniform tokens, paged KV (16), natural acceptance",
                    "tokens_generated": tokens, "mean_acceptance": tokens / (args.steps * B), "context_at_end": L_end,
                    "device_flags": flags},

@@ -86,11 +86,17 @@ typedef struct {
  *   u = [h_last ; E[x_t] ; E[x^_{t+1}] ; ... ; E[x^_{t+i-1}]]   (width (i+1) d)
  * through  z = SiLU(W1 u + b1),  z <- z + SiLU(Wj z + bj) for j = 2..mlp_layers
  * (Hydra++ "Scaling", section 3.1),  logits = Wout z.
- * include_root_embedding = 0 drops E[x_t] from u (width i d). */
+ * include_root_embedding = 0 drops E[x_t] from u (width i d).
+ * medusa = 1 gives the sequentially independent baseline heads of section 2
+ * ("Lightweight heads as a draft model", "Medusa decoding"): u = h_last only
+ * (W1 is [d, d]) and the first layer is residual, z = h_last + SiLU(W1 h_last + b1);
+ * the candidate path is ignored, so all nodes of one depth receive prefixes of
+ * the same ranked list. */
 typedef struct {
     int32_t n_draft_heads;      /* K, 0..HYDRA_MAX_DRAFT_HEADS (0: no draft call)   */
     int32_t mlp_layers;         /* >= 1                                             */
     int32_t include_root_embedding;
+    int32_t medusa;             /* 0 = Hydra heads, 1 = Medusa-style heads          */
 } hydra_heads_desc;
 
 /* Static candidate tree (section 2): host array parent[T], parent[0] = -1,

@@ -35,7 +35,8 @@ class ModelDesc(C.Structure):
 
 
 class HeadsDesc(C.Structure):
-    _fields_ = [("n_draft_heads", C.c_int32), ("mlp_layers", C.c_int32), ("include_root_embedding", C.c_int32)]
+    _fields_ = [("n_draft_heads", C.c_int32), ("mlp_layers", C.c_int32), ("include_root_embedding", C.c_int32),
+                ("medusa", C.c_int32)]
 
 
 class TreeDesc(C.Structure):
@@ -129,10 +130,10 @@ class Hydra:
     """One library context = one (model, heads, tree) triple."""
 
     def __init__(self, *, d, n_layers, n_heads, head_dim, ffn, vocab, dtype, rms_eps=1e-6, rope_theta=10000.0,
-                 max_pos=8192, n_draft_heads=0, mlp_layers=1, include_root_embedding=1,
+                 max_pos=8192, n_draft_heads=0, mlp_layers=1, include_root_embedding=1, medusa=0,
                  parent: Sequence[int] = (-1,), max_batch=1, page_size=16):
         self.model = ModelDesc(d, n_layers, n_heads, head_dim, ffn, vocab, dtype, rms_eps, rope_theta, page_size, max_pos)
-        self.heads = HeadsDesc(n_draft_heads, mlp_layers, include_root_embedding)
+        self.heads = HeadsDesc(n_draft_heads, mlp_layers, include_root_embedding, medusa)
         self.T = len(parent)
         arr = (C.c_int32 * self.T)(*[int(p) for p in parent])
         tree = TreeDesc(self.T, arr)

@@ -27,6 +27,7 @@ static size_t matrix_bytes(const hydra_ctx *c, size_t N, size_t K) {
 static size_t vec_bytes(size_t n) { return align_up(n * 4, 256); }
 
 static int head_in_width(const hydra_ctx *c, int i) {
+    if (c->h.medusa) return c->m.d;                       // Medusa-style heads read h_last only
     return (c->h.include_root_embedding ? i + 1 : i) * c->m.d;
 }
 
@@ -191,6 +192,7 @@ int hydra_create(const hydra_model_desc *m, const hydra_heads_desc *h, const hyd
     if (t->T < 1 || t->T > HYDRA_MAX_T) return fail(HYDRA_E_UNSUPPORTED, "tree: T outside [1, 128]");
     if (h->n_draft_heads < 0 || h->n_draft_heads > HYDRA_MAX_DRAFT_HEADS) return fail(HYDRA_E_UNSUPPORTED, "heads: n_draft_heads outside [0, 8]");
     if (h->mlp_layers < 1 || h->mlp_layers > 9) return fail(HYDRA_E_UNSUPPORTED, "heads: mlp_layers outside [1, 9]");
+    if (h->medusa != 0 && h->medusa != 1) return fail(HYDRA_E_INVALID_ARG, "heads: medusa must be 0 or 1");
     if ((int64_t)m->max_pos * (m->head_dim / 2) * 8 > (int64_t)1 << 31) return fail(HYDRA_E_UNSUPPORTED, "model: max_pos too large");
 
     hydra_ctx *c = new (std::nothrow) hydra_ctx();
@@ -350,7 +352,8 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
         if (Mi == 0) continue;
         const int Kin = head_in_width(c, i);
         GemmPlan p;
-        if ((rc = launch_draft_gather(c, s, B, i, h_last, tree_tokens, xa, flags_ptr(c)))) return rc;
+        const bool first_residual = c->h.medusa != 0;       // Medusa-style first layer: z = h_last + SiLU(W1 h_last + b1)
+        if ((rc = launch_draft_gather(c, s, B, i, h_last, tree_tokens, xa, first_residual ? z : nullptr, flags_ptr(c)))) return rc;
         void *cur = xb, *other = xa;
         if (c->bf16) {
             // MLP layers: bias + SiLU (+ residual) fused into the GEMM epilogue, unless splitting K over more
@@ -366,7 +369,7 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
                 }
                 return launch_gemm_bias_silu(c, s, xin, A + w_off, Mi, d, K, (const float *)(A + b_off), z, residual, xout);
             };
-            if ((rc = mlp_layer(xa, c->head[i].w1, c->head[i].b1, Kin, false, xb))) return rc;
+            if ((rc = mlp_layer(xa, c->head[i].w1, c->head[i].b1, Kin, first_residual, xb))) return rc;
             for (int j = 2; j <= c->h.mlp_layers; ++j) {
                 if ((rc = mlp_layer(cur, c->head[i].wl[j - 2], c->head[i].bl[j - 2], d, true, other))) return rc;
                 std::swap(cur, other);
@@ -374,7 +377,7 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
         } else {
             if ((rc = launch_gemm(c, s, xa, A + c->head[i].w1, part, Mi, d, Kin, &p))) return rc;
             const size_t ss = (size_t)align_up(Mi, 32) * gemm_npad(c, d);
-            if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].b1), z, false, xb, Mi))) return rc;
+            if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].b1), z, first_residual, xb, Mi))) return rc;
             for (int j = 2; j <= c->h.mlp_layers; ++j) {
                 if ((rc = launch_gemm(c, s, cur, A + c->head[i].wl[j - 2], part, Mi, d, d, &p))) return rc;
                 if ((rc = launch_bias_silu(c, s, part, p.splits, gemm_npad(c, d), ss, (const float *)(A + c->head[i].bl[j - 2]), z, true, other, Mi))) return rc;

@@ -23,18 +23,23 @@ int launch_draft_root(hydra_ctx *c, hipStream_t s, int B, const int32_t *root, i
 //   u = [h_last ; E[tok(p_0)] ; ... ; E[tok(p_{i-1})]],  p_0 = root, p_{i-1} = n,
 // concatenated on the feature axis.  Row r = b * n_expand + j.
 // grid = (rows, segments); segment 0 copies h_last, segment s >= 1 one embedding.
+// Medusa-style heads (section 2) have segment 0 only; z_out then also receives
+// h_last in fp32, the residual term of their first layer.
 // ---------------------------------------------------------------------------
 template <bool BF>
 __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_root, const float *h_last,
                                     const int32_t *tree_tokens, const typename Elem<BF>::type *E, int d, int V,
-                                    int Kin, typename Act<BF>::type *out, int32_t *flags) {
+                                    int Kin, typename Act<BF>::type *out, float *z_out, int32_t *flags) {
     const int ne = tree->n_expand[phase];
     const int r = blockIdx.x, seg = blockIdx.y;
     const int b = r / ne, j = r - b * ne;
     const int n = tree->expand_nodes[tree->expand_off[phase] + j];
     if (seg == 0) {
-        for (int k = threadIdx.x; k < d; k += blockDim.x)
-            Act<BF>::st(out, x_index<BF>(r, k, Kin), h_last[(size_t)b * d + k]);
+        for (int k = threadIdx.x; k < d; k += blockDim.x) {
+            const float v = h_last[(size_t)b * d + k];
+            Act<BF>::st(out, x_index<BF>(r, k, Kin), v);
+            if (z_out) z_out[(size_t)r * d + k] = v;
+        }
         return;
     }
     // embedding of the path node at depth dd; n itself has depth phase-1
@@ -51,15 +56,15 @@ __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_
 }
 
 int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const float *h_last,
-                        const int32_t *tree_tokens, void *x_out, int32_t *flags) {
+                        const int32_t *tree_tokens, void *x_out, float *z_out, int32_t *flags) {
     const int ne = c->tree.n_expand[phase];
     const int inc = c->h.include_root_embedding ? 1 : 0;
-    const int nseg = 1 + (inc ? phase : phase - 1);
+    const int nseg = c->h.medusa ? 1 : 1 + (inc ? phase : phase - 1);
     const int Kin = nseg * c->m.d;
     dim3 grid(B * ne, nseg), block(256);
     const void *E = c->arena + c->off_embed;
-    if (c->bf16) hipLaunchKernelGGL(draft_gather_kernel<true>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const bf16_t *)E, c->m.d, c->m.vocab, Kin, (a16_t *)x_out, flags);
-    else         hipLaunchKernelGGL(draft_gather_kernel<false>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const float *)E, c->m.d, c->m.vocab, Kin, (float *)x_out, flags);
+    if (c->bf16) hipLaunchKernelGGL(draft_gather_kernel<true>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const bf16_t *)E, c->m.d, c->m.vocab, Kin, (a16_t *)x_out, z_out, flags);
+    else         hipLaunchKernelGGL(draft_gather_kernel<false>, grid, block, 0, s, tree_dev(c), phase, inc, h_last, tree_tokens, (const float *)E, c->m.d, c->m.vocab, Kin, (float *)x_out, z_out, flags);
     HYDRA_LAUNCH_CHECK("draft_gather_kernel");
     return HYDRA_OK;
 }

@@ -156,7 +156,7 @@ int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_k
 // draft
 int launch_draft_root(hydra_ctx *c, hipStream_t s, int B, const int32_t *root, int32_t *tree_tokens);
 int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const float *h_last,
-                        const int32_t *tree_tokens, void *x_out, int32_t *flags);
+                        const int32_t *tree_tokens, void *x_out, float *z_out, int32_t *flags);
 int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                      const float *bias, float *z, bool residual, void *x_out, int M);
 int launch_topk(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,

@@ -110,7 +110,7 @@ class Session:
         s = self.shape
         ctx = hb.Hydra(d=s.d, n_layers=s.NL, n_heads=s.H, head_dim=s.Dh, ffn=s.F, vocab=s.V, dtype=self.dtype_code,
                        rms_eps=s.rms_eps, rope_theta=s.rope_theta, max_pos=self._max_pos, n_draft_heads=s.K,
-                       mlp_layers=s.mlp_layers, include_root_embedding=s.include_root_embedding,
+                       mlp_layers=s.mlp_layers, include_root_embedding=s.include_root_embedding, medusa=getattr(s, "medusa", 0),
                        parent=parent, max_batch=self.B)
         self._ctx[name] = ctx
         self._out[name] = _Outputs(ctx, self.B, s.d, s.V, self.dev, self.want_logits)
