@@ -61,7 +61,7 @@ template <int DH, bool PACKED>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const u32x4_t *__restrict__ qbuf, const a16_t *__restrict__ kpages, const a16_t *__restrict__ vpages,
     const int32_t *__restrict__ page_table, int max_pages, int n_pages, int layer, const int32_t *__restrict__ seq_len,
-    const TreeDev *__restrict__ tree, int T, int H, int QW, float scale, float *__restrict__ apart, void *out,
+    const TreeDev *__restrict__ tree, int T, int H, int QW, int qsplit, float scale, float *__restrict__ apart, void *out,
     int32_t *flags) {
     constexpr int KS = DH / 16, DT = DH / 32;
     extern __shared__ float lds[];
@@ -72,9 +72,13 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const int h = blockIdx.y, b = blockIdx.z;
     const int QTtot = (T + 31) >> 5;
     const int Tq = QTtot * 32;
-    const int units = gridDim.x * KWV;
-    const int unit = blockIdx.x * KWV + kwv;
-    const bool active = qw < QTtot;                        // idle waves only take part in the barriers
+    // qsplit: the workgroups of a (row, head) take different 32-query tiles and each sees all keys (no partial
+    // records, no merge kernel); otherwise they split the keys and every workgroup holds all query tiles
+    const int qtile = qsplit ? (int)blockIdx.x * QW + qw : qw;
+    const int key_wgs = qsplit ? 1 : (int)gridDim.x;
+    const int units = key_wgs * KWV;
+    const int unit = (qsplit ? 0 : (int)blockIdx.x) * KWV + kwv;
+    const bool active = qtile < QTtot;                     // idle waves only take part in the barriers
     const int32_t *pt = page_table + (size_t)b * max_pages;
     // Everything whose address does not depend on the row's length is requested before the length is known:
     // the queries, the ancestor masks and the page-table entries of this wave's first two key tiles (the table
@@ -83,10 +87,10 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     uint64_t anc0 = 0ull, anc1 = 0ull;
     int pg[2][2] = {{0, 0}, {0, 0}};
     if (active) {
-        const size_t blk = (((size_t)b * H + h) * QTtot + qw) * KS;
+        const size_t blk = (((size_t)b * H + h) * QTtot + qtile) * KS;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qreg[s] = qbuf[(blk + s) * 64 + lane];
-        const int query = qw * 32 + col;
+        const int query = qtile * 32 + col;
         if (query < T) { anc0 = tree->anc[query][0]; anc1 = tree->anc[query][1]; }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -222,8 +226,8 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     __syncthreads();
     if (!active) return;
     // wave kwv finishes bands dt = kwv, kwv + KWV, ...
-    const int query = qw * 32 + col;
-    const bool final_out = gridDim.x == 1;
+    const int query = qtile * 32 + col;
+    const bool final_out = key_wgs == 1;
     const float inv = final_out ? 1.0f / l_tot : 1.0f;
     float *rec = apart + ((((size_t)b * H + h) * gridDim.x) + blockIdx.x) * apart_record(Tq, DH);
     for (int dt = kwv; dt < DT; dt += KWV) {
@@ -343,16 +347,21 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     }
     const int T = c->tree.T, H = c->m.n_heads, Dh = c->m.head_dim;
     const int QTtot = ceil_div(T, 32);
-    const int QW = QTtot >= 3 ? 4 : QTtot;                 // 1, 2 or 4 query waves
-    const int KWV = ATTN_WAVES / QW;
-    // workgroups per (b, h): a CU streams at most ~45 GB/s, so the keys of one head are spread over
-    // several CUs; a key-split wave takes about two 32-key tiles
-    int wgs = 1;
+    int QW = QTtot >= 3 ? 4 : QTtot;                       // 1, 2 or 4 query waves
+    int KWV = ATTN_WAVES / QW;
     const int len = kv->seq_len_hint > 0 ? kv->seq_len_hint : c->m.max_pos;
     const int tiles = ceil_div(len + T, 32);
-    wgs = ceil_div(tiles, KWV * 2);
-    if (wgs > units_max) wgs = units_max;
-    if (wgs < 1) wgs = 1;
+    // Short contexts: one workgroup per 32-query tile, its 8 waves split the keys (up to five 32-key tiles each) and
+    // the result goes straight out.  Longer ones: a CU streams at most ~45 GB/s, so the keys of one head are spread
+    // over several workgroups (about two tiles per wave) whose partial records attn_merge_kernel combines.
+    int wgs = 1, qsplit = 0;
+    if (tiles <= ATTN_WAVES * 5) {
+        qsplit = 1; QW = 1; KWV = ATTN_WAVES; wgs = QTtot;
+    } else {
+        wgs = ceil_div(tiles, KWV * 2);
+        if (wgs > units_max) wgs = units_max;
+        if (wgs < 1) wgs = 1;
+    }
     dim3 grid(wgs, H, B), block(ATTN_WAVES * 64);
     const float scale = 1.0f / sqrtf((float)Dh);
     const size_t lds = attn_lds_bytes(Dh);
@@ -361,12 +370,12 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
 #define ATTN_CASE(DHv, Pv)                                                                                           \
     hipLaunchKernelGGL((attn_bf16_kernel<DHv, Pv>), grid, block, lds, s, (const u32x4_t *)qbuf,                       \
                        (const a16_t *)kv->k_pages, (const a16_t *)kv->v_pages, kv->page_table, kv->max_pages,      \
-                       kv->n_pages, layer, seq_len, tree_dev(c), T, H, QW, scale, apart, out, flags)
+                       kv->n_pages, layer, seq_len, tree_dev(c), T, H, QW, qsplit, scale, apart, out, flags)
     if (Dh == 128) { if (packed) ATTN_CASE(128, true); else ATTN_CASE(128, false); }
     else           { if (packed) ATTN_CASE(64, true); else ATTN_CASE(64, false); }
 #undef ATTN_CASE
     HYDRA_LAUNCH_CHECK("attn_bf16_kernel");
-    if (wgs > 1) {
+    if (!qsplit && wgs > 1) {
         const int q_per_wg = 256 / (Dh / 4);
         dim3 mgrid(ceil_div(T, q_per_wg), H, B), mblock(256);
         if (packed) hipLaunchKernelGGL(attn_merge_kernel<true>, mgrid, mblock, 0, s, apart, seq_len, T, H, Dh, wgs, kv->max_pages, out);

@@ -44,7 +44,9 @@ TREES = {"tiny16": lambda: frozen_tree("tiny16"), "prior64": lambda: frozen_tree
                                                ("prior64", 32, 1, 128), ("prior64", 33, 2, 128), ("prior64", 500, 1, 128),
                                                ("tiny16", 17, 3, 128), ("prior128", 200, 1, 128), ("random70", 77, 2, 128),
                                                ("single", 129, 2, 128), ("chain40", 8, 1, 128), ("prior64", 95, 2, 64),
-                                               ("prior32", 1000, 1, 128)])
+                                               ("prior32", 1000, 1, 128),
+                                               # beyond ~1200 keys the keys of a head are split over workgroups and merged
+                                               ("prior64", 1500, 1, 128), ("prior128", 1400, 2, 64), ("tiny16", 2500, 1, 128)])
 def test_tree_attention_sharp_scores(tree_name, L, B, Dh):
     print("case", tree_name, L, B, Dh, flush=True)
     cfg = bf16_shape(H=256 // Dh, Dh=Dh)
