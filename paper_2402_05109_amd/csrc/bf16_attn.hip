@@ -81,11 +81,12 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const bool active = qtile < QTtot;                     // idle waves only take part in the barriers
     const int32_t *pt = page_table + (size_t)b * max_pages;
     // Everything whose address does not depend on the row's length is requested before the length is known:
-    // the queries, the ancestor masks and the page-table entries of this wave's first two key tiles (the table
+    // the queries, the ancestor masks and the page-table entries of this wave's first key tiles (the table
     // has max_pages entries for every row, so the reads are in bounds; entries past the row's pages are not used).
+    enum { PG_AHEAD = 5 };                                 // page ids of this many key tiles per wave are fetched up front
     u32x4_t qreg[KS];
     uint64_t anc0 = 0ull, anc1 = 0ull;
-    int pg[2][2] = {{0, 0}, {0, 0}};
+    int pg[PG_AHEAD][2];
     if (active) {
         const size_t blk = (((size_t)b * H + h) * QTtot + qtile) * KS;
 #pragma unroll
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
         const int query = qtile * 32 + col;
         if (query < T) { anc0 = tree->anc[query][0]; anc1 = tree->anc[query][1]; }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < PG_AHEAD; ++j) {
             const int t = unit + j * units;
             pg[j][0] = pt[min(2 * t, max_pages - 1)];
             pg[j][1] = pt[min(2 * t + 1, max_pages - 1)];
@@ -119,13 +120,19 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
         KVTile<DH> cur, nxt;
         // second page of a tile: absent when the row ends inside the first one (its keys are masked; any valid page will do)
         load_kv_tile<DH>(cur, kpages, vpages, pg[0][0], (2 * unit + 1 < row_pages) ? pg[0][1] : pg[0][0], layer, n_pages, H, h, lane);
-        for (int t = unit; t < n_tiles; t += units) {
+        int it = 0;                                        // index of tile t among this wave's tiles
+        for (int t = unit; t < n_tiles; t += units, ++it) {
             const bool more = t + units < n_tiles;
             if (more) {
                 const int tn = t + units;
                 int p0, p1;
-                if (t == unit) { p0 = pg[1][0]; p1 = pg[1][1]; }
-                else           { p0 = pt[2 * tn]; p1 = (2 * tn + 1 < row_pages) ? pt[2 * tn + 1] : p0; }
+                switch (it + 1) {                          // wave-uniform; keeps the page ids in scalar registers
+                    case 1: p0 = pg[1][0]; p1 = pg[1][1]; break;
+                    case 2: p0 = pg[2][0]; p1 = pg[2][1]; break;
+                    case 3: p0 = pg[3][0]; p1 = pg[3][1]; break;
+                    case 4: p0 = pg[4][0]; p1 = pg[4][1]; break;
+                    default: p0 = pt[2 * tn]; p1 = (2 * tn + 1 < row_pages) ? pt[2 * tn + 1] : p0; break;
+                }
                 if (2 * tn + 1 >= row_pages) p1 = p0;
                 load_kv_tile<DH>(nxt, kpages, vpages, p0, p1, layer, n_pages, H, h, lane);
             }
