@@ -105,15 +105,15 @@ def main():
     ap.add_argument("--tree", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="candidate-tree size (nodes with the root); 0 = the configuration's own (the headline workload)")
     ap.add_argument("--medusa", action="store_true",
-                    help="Medusa-style draft heads (h_last only, residual single-layer MLP) instead of Hydra heads: the baseline draft cost")
+                    help="Medusa-style draft heads (h_last only, one hidden layer with a skip connection) instead of Hydra heads: the baseline draft cost")
     ap.add_argument("--typical", action="store_true",
                     help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards by batch row with no collectives; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path shards by batch row with no collectives, "
+              "so N GPUs are N independent copies of this run); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor, uniform_tokens

@@ -237,9 +237,9 @@ def head_logits(model, i, h_last, path_tokens):
     include_root_embedding = 0 the embedding of x_t is left out of u.
 
     model.medusa (paper, section 2, "Lightweight heads as a draft model" and "Medusa
-    decoding"): the head sees h_{t-1} only, p_draft = f_draft,i(h_{t-1}), and its
-    first layer is a single-layer MLP with a residual connection,
-    z = h + SiLU(W1 h + b1) with W1 [d, d]; the path tokens are ignored.
+    decoding"): the head sees h_{t-1} only, p_draft = f_draft,i(h_{t-1}); it has one
+    hidden layer with a skip connection around it, z = h + SiLU(W1 h + b1) with
+    W1 [d, d]; the path tokens are ignored.
     """
     m = model
     if m.medusa:

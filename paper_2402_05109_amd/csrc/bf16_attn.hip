@@ -16,13 +16,15 @@
 // of K and V (device_common.h) makes both A operands single coalesced
 // 16-byte-per-lane loads straight from the cache pages.
 //
-// A workgroup is 8 waves on one (b, h): QW of them take different 32-query
-// tiles, and for each query tile 8/QW waves split the keys (32-key tiles taken
-// round-robin, next tile prefetched while the current one is multiplied).  The
-// key-split waves are merged through LDS.  With one workgroup per (b, h)
-// (gridDim.x == 1) the result goes straight out as the next GEMM's input;
-// longer contexts use several workgroups and leave (max, sum, O) records that
-// attn_merge_kernel combines.
+// A workgroup is 8 waves on one (b, h).  Two launch shapes:
+//   short contexts (up to ~1200 keys): one workgroup per 32-query tile; its 8
+//     waves split the keys (32-key tiles taken round-robin, next tile prefetched
+//     while the current one is multiplied), are merged through LDS, and the
+//     result goes straight out as the next GEMM's input: one kernel, no partial
+//     records.  A CU streams at most ~45 GB/s, which is what bounds this shape;
+//   longer contexts: QW waves of a workgroup take different query tiles, 8/QW
+//     waves split the keys, and several workgroups per (b, h) split the keys
+//     further; each leaves a (max, sum, O) record that attn_merge_kernel combines.
 #include "device_common.h"
 #include "internal.h"
 

@@ -96,7 +96,7 @@ struct EpiPlain {
 };
 
 // Residual branch end: x += acc.  Also leaves what the next RMSNorm'd GEMM needs:
-// xg = bf16(x * gain) in GEMM input order (the 1/rms factor commutes with the
+// xg = half(x * gain) in GEMM input order (the 1/rms factor commutes with the
 // contraction and is applied by the consumer) and ss[band][row] = sum over the
 // band's 32 columns of x^2.
 struct EpiResid {
@@ -478,7 +478,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
     return launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
-// x += X W^T, then xg = bf16(x * gain) and the per-band sums of squares.  Either fused into the GEMM
+// x += X W^T, then xg = half(x * gain) and the per-band sums of squares.  Either fused into the GEMM
 // epilogue (one workgroup owns a band for all of K) or, when the plan splits K over workgroups to fill
 // the chip, as S partial outputs added by a small second kernel.
 __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,

@@ -8,8 +8,8 @@
 namespace hydra {
 
 // ---------------------------------------------------------------------------
-// x[m, :] = E[token[m], :]      (tree verification: "packing all of the tree's
-// tokens into a single input sequence", paper section 2)
+// x[m, :] = E[token[m], :]      (tree verification feeds all T candidate tokens
+// of a row as one packed input; paper, section 2, "Tree decoding")
 // ---------------------------------------------------------------------------
 template <bool BF>
 __global__ void embed_kernel(const typename Elem<BF>::type *E, const int32_t *tokens, float *x, int d, int V,
@@ -37,7 +37,7 @@ __device__ __forceinline__ float row_rstd_block(const RowScale &rs, int m, float
     return sh[0];
 }
 
-// bf16 family: x = E[token]; xg = bf16(x * gain) as GEMM input; ss[band][row] = sum of x^2 over the band
+// bf16 family: x = E[token]; xg = half(x * gain) as GEMM input; ss[band][row] = sum of x^2 over the band
 __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const int32_t *tokens, float *x,
                                                           const float *gain, a16_t *xg, float *ss, int Mpad, int d,
                                                           int V, int32_t *flags) {

@@ -1,5 +1,5 @@
-"""GPU parity of hydra_draft_tree with Medusa-style heads (paper, section 2: p_draft = f_draft,i(h_{t-1}), a
-single-layer MLP with a residual connection; section 3: no sequential dependence) against the oracle.
+"""GPU parity of hydra_draft_tree with Medusa-style heads (paper, section 2: p_draft = f_draft,i(h_{t-1}), one
+hidden layer with a skip connection; section 3: no sequential dependence) against the oracle.
 
 fp32 family: drafted ids exact.  16-bit family: ids exact or a valid reordering inside the 2e-2 tolerance
 (counted).  On both the drafted lists must not depend on the candidate path.

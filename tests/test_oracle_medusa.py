@@ -1,6 +1,6 @@
 """Pins for the oracle's Medusa-style draft heads (paper, section 2: "Lightweight heads as a draft model",
-"Medusa decoding"; section 3, the displayed independence equation): p_draft = f_draft,i(h_{t-1}), a single-layer
-MLP with a residual connection, no dependence on the candidate path.
+"Medusa decoding"; section 3, the displayed independence equation): p_draft = f_draft,i(h_{t-1}), one hidden
+layer with a skip connection around it, no dependence on the candidate path.
 """
 import numpy as np
 import torch
