@@ -268,6 +268,7 @@ def main():
                      "launches_timed": n_launch, "avg_launch_us": ms_sum / max(n_launch, 1) * 1e3,
                      "algorithmic_bytes_per_launch": w_bytes / max(n_launch, 1),
                      "empty_event_bracket_us": empty_bracket_us,
+                     "achieved_net_of_empty_bracket": (w_bytes / n_launch) / max((ms_sum / n_launch * 1e3 - empty_bracket_us) * 1e-6, 1e-9) / 1e9 if n_launch else 0.0,
                      "scope": "the 129 GEMM launches of one tree_verify_forward (4 per layer + LM head), averaged over 8 calls"},
     }
     if not args.no_cpu_baseline:

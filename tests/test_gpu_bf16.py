@@ -152,7 +152,8 @@ def _audit_children(logits, kids, tol_abs):
     return False
 
 
-@pytest.mark.parametrize("tree_name,B,mlp", [("prior64", 1, 1), ("prior64", 2, 4), ("tiny16", 5, 2), ("prior128", 1, 1), ("single", 1, 1)])
+@pytest.mark.parametrize("tree_name,B,mlp", [("prior64", 1, 1), ("prior64", 2, 4), ("tiny16", 5, 2), ("prior128", 1, 1), ("single", 1, 1),
+                                             ("prior64", 16, 2)])                          # 336 draft rows in the widest phase
 def test_draft_tree_matches_oracle(tree_name, B, mlp):
     print("case", tree_name, B, mlp, flush=True)
     cfg = bf16_shape(mlp_layers=mlp)
@@ -184,7 +185,8 @@ def test_draft_tree_matches_oracle(tree_name, B, mlp):
 
 
 @pytest.mark.parametrize("tree_name,B,L", [("prior64", 1, 37), ("prior64", 2, 64), ("tiny16", 3, 5), ("single", 2, 90),
-                                            ("prior128", 1, 130), ("chain40", 1, 0), ("random70", 2, 33)])
+                                            ("prior128", 1, 130), ("chain40", 1, 0), ("random70", 2, 33),
+                                            ("prior64", 16, 21), ("prior128", 3, 9)])      # 1024 and 384 rows: several row groups per GEMM
 def test_tree_verify_forward_teacher_forced(tree_name, B, L):
     print("case", tree_name, B, L, flush=True)
     cfg = bf16_shape()
