@@ -423,7 +423,7 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
         // squares; the 1/rms factor of each RMSNorm is applied by the consumer of the following GEMM.
         float *ss = (float *)(W + w.ss);
         const int Mpad = (int)align_up(std::max<size_t>(M, 1), 128);
-        const RowScale rs = {ss, d / 32, Mpad, d, c->m.rms_eps};
+        RowScale rs = {ss, 1, Mpad, d, c->m.rms_eps};        // rs.nb: rows of ss the last producer filled (1 = a complete sum per row)
         const float *gain0 = (const float *)(A + c->layer[0].attn_norm);
         if (src.tokens) { if ((rc = launch_embed_prep(c, s, src.tokens, x, gain0, xa, ss, Mpad, M, flags))) return rc; }
         else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, gain0, xa, ss, Mpad, flags))) return rc; }
@@ -432,9 +432,9 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
             const float *next_gain = (const float *)(A + (l + 1 < c->m.n_layers ? c->layer[l + 1].attn_norm : c->off_final_norm));
             if ((rc = launch_gemm_qkv_rope(c, s, xa, A + o.wqkv, M, rs, l, seq_len, kv, qbuf, flags))) return rc;
             if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xb, nullptr, flags))) return rc;
-            if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad, part))) return rc;
-            if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, d / 32, Mpad, xb))) return rc;
-            if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad, part))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad, part, &rs.nb))) return rc;
+            if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, rs.nb, Mpad, xb))) return rc;
+            if ((rc = launch_gemm_resid(c, s, xb, A + o.wdown, M, d, F, x, next_gain, xa, ss, Mpad, part, &rs.nb))) return rc;
         }
         if (!lm_tail) return HYDRA_OK;
         if ((rc = launch_final_hidden(c, s, x, (const float *)(A + c->off_final_norm), rs, hidden, M))) return rc;

@@ -478,34 +478,41 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
     return launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
-// x += X W^T, then xg = half(x * gain) and the per-band sums of squares.  Either fused into the GEMM
+// x += X W^T, then xg = half(x * gain) and the sums of squares (*ss_bands rows of ss: one per band, or one per 1024-column chunk).  Either fused into the GEMM
 // epilogue (one workgroup owns a band for all of K) or, when the plan splits K over workgroups to fill
 // the chip, as S partial outputs added by a small second kernel.
+// One workgroup per (row, 1024-column chunk): the chunk's sum of squares goes to ss[chunk][row], so the consumers'
+// row-scale gathering reads d / 1024 values per row instead of one per 32-column band.
 __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
                                                           int ld, size_t split_stride, const float *__restrict__ gain,
                                                           a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad,
                                                           int d) {
+    __shared__ float red[4];
     const int m = blockIdx.y;
     const int k = (blockIdx.x * 256 + threadIdx.x) * 4;
-    if (k >= d) return;                                       // d % 32 == 0: a 32-lane group is all in or all out
-    f32x4_t a = *reinterpret_cast<const f32x4_t *>(x + (size_t)m * d + k);
-    for (int sp = 0; sp < S; ++sp) {
-        const f32x4_t q = *reinterpret_cast<const f32x4_t *>(part + (size_t)sp * split_stride + (size_t)m * ld + k);
-        a[0] += q[0]; a[1] += q[1]; a[2] += q[2]; a[3] += q[3];
+    float sq = 0.f;
+    if (k < d) {                                              // d % 32 == 0: a group of 8 lanes is all in or all out
+        f32x4_t a = *reinterpret_cast<const f32x4_t *>(x + (size_t)m * d + k);
+        for (int sp = 0; sp < S; ++sp) {
+            const f32x4_t q = *reinterpret_cast<const f32x4_t *>(part + (size_t)sp * split_stride + (size_t)m * ld + k);
+            a[0] += q[0]; a[1] += q[1]; a[2] += q[2]; a[3] += q[3];
+        }
+        *reinterpret_cast<f32x4_t *>(x + (size_t)m * d + k) = a;
+        const f32x4_t gn = *reinterpret_cast<const f32x4_t *>(gain + k);
+        const uint32_t lo = f2a_pack(a[0] * gn[0], a[1] * gn[1]);
+        const uint32_t hi = f2a_pack(a[2] * gn[2], a[3] * gn[3]);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(xg + x_index<true>(m, k, d));     // 4 consecutive k share an 8-run
+        dst[0] = lo; dst[1] = hi;
+        sq = a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
     }
-    *reinterpret_cast<f32x4_t *>(x + (size_t)m * d + k) = a;
-    const f32x4_t gn = *reinterpret_cast<const f32x4_t *>(gain + k);
-    const uint32_t lo = f2a_pack(a[0] * gn[0], a[1] * gn[1]);
-    const uint32_t hi = f2a_pack(a[2] * gn[2], a[3] * gn[3]);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(xg + x_index<true>(m, k, d));     // 4 consecutive k share an 8-run
-    dst[0] = lo; dst[1] = hi;
-    float sq = a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
-    sq += __shfl_xor(sq, 1, 64); sq += __shfl_xor(sq, 2, 64); sq += __shfl_xor(sq, 4, 64);   // 8 lanes = one 32-column band
-    if ((threadIdx.x & 7) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
+    sq = wave_sum(sq);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0) ss[(size_t)blockIdx.x * Mpad + m] = red[0] + red[1] + red[2] + red[3];
 }
 
 int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *x,
-                      const float *gain, void *xg, float *ss, int Mpad, float *part) {
+                      const float *gain, void *xg, float *ss, int Mpad, float *part, int *ss_bands) {
     GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_PLAIN);
     if (p.splits > 1) {
         const int npad = gemm_npad(c, N);
@@ -516,8 +523,10 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
         hipLaunchKernelGGL(resid_norm_kernel, dim3(ceil_div(N, 1024), M), dim3(256), 0, s, x, part, p.splits, npad, stride,
                            gain, (a16_t *)xg, ss, Mpad, N);
         HYDRA_LAUNCH_CHECK("resid_norm_kernel");
+        *ss_bands = ceil_div(N, 1024);       // one partial sum per 1024-column chunk
         return HYDRA_OK;
     }
+    *ss_bands = N / 32;                      // the fused epilogue leaves one partial sum per 32-column band
     p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
     EpiResid epi{x, N, gain, (a16_t *)xg, ss, Mpad};
     return launch_bf16<EpiResid, NT_ANY>(c, s, X, W, M, N, K, p, epi);

@@ -37,7 +37,16 @@ __device__ __forceinline__ float row_rstd_block(const RowScale &rs, int m, float
     return sh[0];
 }
 
-// bf16 family: x = E[token]; xg = half(x * gain) as GEMM input; ss[band][row] = sum of x^2 over the band
+// sum over the 256 threads of a workgroup in a fixed order, written by thread 0
+__device__ __forceinline__ void block256_row_sum(float v, float *dst) {
+    __shared__ float red[4];
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) *dst = red[0] + red[1] + red[2] + red[3];
+}
+
+// bf16 family: x = E[token]; xg = half(x * gain) as GEMM input; ss[row] = sum of x^2 over the row
 __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const int32_t *tokens, float *x,
                                                           const float *gain, a16_t *xg, float *ss, int Mpad, int d,
                                                           int V, int32_t *flags) {
@@ -49,6 +58,7 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
     }
     typedef __attribute__((ext_vector_type(4))) uint32_t u4;
     typedef __attribute__((ext_vector_type(4))) float f4;
+    float sq = 0.f;
     // a thread takes 8 consecutive columns (d is a multiple of 128): one 16-byte load, one 16-byte store of xg
     for (int k = threadIdx.x * 8; k < d; k += 256 * 8) {
         const u4 raw = *reinterpret_cast<const u4 *>(E + (size_t)tok * d + k);
@@ -61,12 +71,10 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
         const u4 pk = {f2a_pack(v[0] * g0[0], v[1] * g0[1]), f2a_pack(v[2] * g0[2], v[3] * g0[3]),
                        f2a_pack(v[4] * g1[0], v[5] * g1[1]), f2a_pack(v[6] * g1[2], v[7] * g1[3])};
         *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
-        float sq = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) sq += v[q] * v[q];
-        sq += __shfl_xor(sq, 1, 64); sq += __shfl_xor(sq, 2, 64);           // 4 threads = one 32-column band
-        if ((threadIdx.x & 3) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
     }
+    block256_row_sum(sq, ss + m);
 }
 
 int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
@@ -393,7 +401,7 @@ int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_k
 // layer input is hidden[b, path[b][min(j, n_acc[b]-1)]]: positions past the
 // accepted length repeat the last accepted state (they sit after every valid
 // position in the chain, so nothing valid can see them).  Leaves x and, in the
-// 16-bit family, the GEMM input xg = half(x * gain) and the per-band sums of
+// 16-bit family, the GEMM input xg = half(x * gain) and the row's sum of
 // squares, exactly as embed_prep_kernel does for token embeddings.
 // ---------------------------------------------------------------------------
 template <bool BF>
@@ -418,6 +426,7 @@ __global__ __launch_bounds__(256) void gather_prep_kernel(const float *__restric
     }
     const float *src = hidden + ((size_t)b * T_src + node) * d;
     if (BF) {
+        float sq = 0.f;
         for (int k = threadIdx.x * 8; k < d; k += 256 * 8) {          // d is a multiple of 128
             const f4 v0 = *reinterpret_cast<const f4 *>(src + k), v1 = *reinterpret_cast<const f4 *>(src + k + 4);
             const f4 g0 = *reinterpret_cast<const f4 *>(gain + k), g1 = *reinterpret_cast<const f4 *>(gain + k + 4);
@@ -426,10 +435,9 @@ __global__ __launch_bounds__(256) void gather_prep_kernel(const float *__restric
             const u4 pk = {f2a_pack(v0[0] * g0[0], v0[1] * g0[1]), f2a_pack(v0[2] * g0[2], v0[3] * g0[3]),
                            f2a_pack(v1[0] * g1[0], v1[1] * g1[1]), f2a_pack(v1[2] * g1[2], v1[3] * g1[3])};
             *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
-            float sq = v0[0] * v0[0] + v0[1] * v0[1] + v0[2] * v0[2] + v0[3] * v0[3] + v1[0] * v1[0] + v1[1] * v1[1] + v1[2] * v1[2] + v1[3] * v1[3];
-            sq += __shfl_xor(sq, 1, 64); sq += __shfl_xor(sq, 2, 64);
-            if ((threadIdx.x & 3) == 0) ss[(size_t)(k >> 5) * Mpad + m] = sq;
+            sq += v0[0] * v0[0] + v0[1] * v0[1] + v0[2] * v0[2] + v0[3] * v0[3] + v1[0] * v1[0] + v1[1] * v1[1] + v1[2] * v1[2] + v1[3] * v1[3];
         }
+        block256_row_sum(sq, ss + m);
     } else {
         for (int k = threadIdx.x; k < d; k += 256) x[(size_t)m * d + k] = src[k];
     }

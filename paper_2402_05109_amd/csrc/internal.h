@@ -110,7 +110,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
 int gemm_npad(const hydra_ctx *c, int N);   // row stride of `part` for N outputs
 // bf16 family, fused epilogues (see bf16_gemm.hip)
 int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *x,
-                      const float *gain, void *xg, float *ss, int Mpad, float *part);
+                      const float *gain, void *xg, float *ss, int Mpad, float *part, int *ss_bands);
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act);
 int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
