@@ -34,7 +34,22 @@ __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_
     const int r = blockIdx.x, seg = blockIdx.y;
     const int b = r / ne, j = r - b * ne;
     const int n = tree->expand_nodes[tree->expand_off[phase] + j];
+    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    typedef __attribute__((ext_vector_type(4))) float f4;
     if (seg == 0) {
+        if (BF) {                                               // 8 columns per thread: one 16-byte store into the operand tile
+            for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+                const f4 v0 = *reinterpret_cast<const f4 *>(h_last + (size_t)b * d + k);
+                const f4 v1 = *reinterpret_cast<const f4 *>(h_last + (size_t)b * d + k + 4);
+                const u4 pk = {f2a_pack(v0[0], v0[1]), f2a_pack(v0[2], v0[3]), f2a_pack(v1[0], v1[1]), f2a_pack(v1[2], v1[3])};
+                *reinterpret_cast<u4 *>(reinterpret_cast<a16_t *>(out) + x_index<true>(r, k, Kin)) = pk;
+                if (z_out) {
+                    *reinterpret_cast<f4 *>(z_out + (size_t)r * d + k) = v0;
+                    *reinterpret_cast<f4 *>(z_out + (size_t)r * d + k + 4) = v1;
+                }
+            }
+            return;
+        }
         for (int k = threadIdx.x; k < d; k += blockDim.x) {
             const float v = h_last[(size_t)b * d + k];
             Act<BF>::st(out, x_index<BF>(r, k, Kin), v);
@@ -50,6 +65,16 @@ __global__ void draft_gather_kernel(const TreeDev *tree, int phase, int include_
     if (tok < 0 || tok >= V) {
         if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_TOKEN);
         tok = 0;
+    }
+    if (BF) {
+        for (int k = threadIdx.x * 8; k < d; k += blockDim.x * 8) {
+            const u4 raw = *reinterpret_cast<const u4 *>(reinterpret_cast<const bf16_t *>(E) + (size_t)tok * d + k);     // 8 bfloat16
+            u4 pk;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) pk[q] = f2a_pack(__uint_as_float(raw[q] << 16), __uint_as_float(raw[q] & 0xffff0000u));
+            *reinterpret_cast<u4 *>(reinterpret_cast<a16_t *>(out) + x_index<true>(r, seg * d + k, Kin)) = pk;
+        }
+        return;
     }
     for (int k = threadIdx.x; k < d; k += blockDim.x)
         Act<BF>::st(out, x_index<BF>(r, seg * d + k, Kin), Elem<BF>::ld(E, (size_t)tok * d + k));
