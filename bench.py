@@ -117,6 +117,9 @@ def main():
               "so N GPUs are N independent copies of this run); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    if not os.path.exists(os.path.join(ROOT, "paper_2402_05109_amd", "libhydra.so")):      # nothing built yet: build, then load
+        from paper_2402_05109_amd.build import build_library
+        build_library(verbose=False)
     from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor, uniform_tokens
     from paper_2402_05109_amd.session import Session
 

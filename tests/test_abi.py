@@ -37,6 +37,7 @@ GOOD = dict(d=256, n_layers=2, n_heads=4, head_dim=64, ffn=688, vocab=1024, dtyp
     (dict(parent=[0, 0]), hb.E_SHAPE), (dict(parent=[-1, 0, 1, 0]), hb.E_SHAPE), (dict(parent=[-1, 1]), hb.E_SHAPE),
     (dict(parent=[-1] + [0] * 128), hb.E_UNSUPPORTED), (dict(parent=[-1] + [0] * 33), hb.E_UNSUPPORTED),
     (dict(n_draft_heads=9), hb.E_UNSUPPORTED), (dict(mlp_layers=0), hb.E_UNSUPPORTED), (dict(max_batch=0), hb.E_INVALID_ARG),
+    (dict(medusa=2), hb.E_INVALID_ARG),
     (dict(dtype=hb.HYDRA_BF16), hb.E_UNSUPPORTED),          # ffn 688 is not a multiple of 128
 ])
 def test_create_rejects_bad_descriptors(change, code):
