@@ -403,6 +403,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     p.cost_us = (float)best_cost;
     const int max_waves = (p.mb * p.nt >= 6) ? 4 : 8;                   // 256-thread workgroups get 512 VGPRs per wave
     p.kw = max_waves;
+    if (p.kw == 8 && p.splits > 1 && KT / (8 * p.splits) >= 16) p.kw = 4;   // split K with long runs left: four waves with twice the run each measured faster
     while (p.kw > 1 && KT / (p.kw * p.splits) < 4) p.kw >>= 1;
     while (p.kw > 1 && ((size_t)GEMM_LDS_SCRATCH + (size_t)p.kw * p.mb * p.nt * 16 * 64) * 4 > 150 * 1024) p.kw >>= 1;   // LDS: KW accumulator copies
     if (mgroups >= 2 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }            // large batch: share X between two N-waves

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
         for (int u = 0; u < GEMM_U; ++u) {
             const int k = min(k0 + u, g.KT - 1);         // clamped: a ragged tail re-reads a valid tile and skips its MFMA
 #pragma unroll
-            for (int i = 0; i < NT; ++i) w[u][i] = wrow[i][(size_t)k * 64];
+            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // used once: streaming load
 #pragma unroll
             for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
         }
