@@ -8,7 +8,7 @@
 // (lane = (k%16)/8*32 + n%32 holds 8 consecutive k); the tiles of one 32-row
 // band are contiguous along k.  X uses the same tile order ("A" operand).
 //
-// Work split.  A wave owns NT bands and a contiguous run of k-steps; it loads
+// Work split.  A wave owns NT bands and every KW-th block of GEMM_U k-steps; it loads
 // its W tiles (and the matching X tiles, which hit in L1/L2) straight into
 // registers with fully coalesced 16-byte-per-lane loads, U k-steps ahead of
 // the MFMAs, and never synchronises with other waves while streaming.  A
@@ -34,6 +34,8 @@
 // registers (rows) at a time:  pair4(x0, x1, a, v0, t, g) with x0[q], x1[q] the registers v0 + q of the
 // tiles (a, 0) and (a, 1).  The 4*MB such items of a band group are shared out over the KW waves.
 #pragma once
+
+#include <type_traits>
 
 #include "device_common.h"
 
@@ -84,8 +86,10 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     t.split = blockIdx.y;
     t.lds = red;
     float *redbuf = red + GEMM_LDS_SCRATCH;
-    const int k_begin = min(g.KT, (int)(blockIdx.y * g.KW + kw) * g.kpw);
-    const int k_end = min(g.KT, k_begin + g.kpw);
+    // the KW waves of a workgroup share the k-range of their split block by block (wave kw takes the blocks
+    // kw, kw + KW, ... of GEMM_U steps), so that together they sweep each band as one contiguous front
+    const int s_begin = min(g.KT, (int)blockIdx.y * g.KW * g.kpw);
+    const int k_end = min(g.KT, s_begin + g.KW * g.kpw);
 
     const u32x4_t *wrow[NT];
 #pragma unroll
@@ -126,25 +130,40 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     };
     // k-blocks of U steps are visited in an order rotated by the workgroup index, so that the
     // workgroups streaming different bands do not all ask the L2 for the same X lines at once
-    const int nblk = (k_end - k_begin + GEMM_U - 1) / GEMM_U;
+    const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
 #ifndef GEMM_EXP_NO_ROTATE
     const int rot = nblk > 0 ? (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk) : 0;
 #else
     const int rot = 0;
 #endif
-    auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return k_begin + q * GEMM_U; };
-    if (nblk > 0) load(wa, xa, kof(0));
-    auto pre = epi.issue(t, g);
-    if (nblk > 1) load(wb, xb, kof(1));
-    auto carry = epi.prologue(pre, t, g);
-    for (int j = 0; j < nblk; j += 2) {
-        compute(wa, xa, kof(j));
-        if (j + 2 < nblk) load(wa, xa, kof(j + 2));
-        if (j + 1 < nblk) {
-            compute(wb, xb, kof(j + 1));
-            if (j + 3 < nblk) load(wb, xb, kof(j + 3));
+    auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
+    // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
+    // unconditional: only then can the compiler count how many loads are younger than the set it is about to
+    // use, and wait for exactly that set instead of draining the queue (a refill behind a condition makes it
+    // assume the worst, which turns the double buffer into issue-then-wait).
+    auto stream = [&](auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
+        if (STEADY || nblk > 0) load(wa, xa, kof(0));
+        auto pre = epi.issue(t, g);
+        if (STEADY || nblk > 1) load(wb, xb, kof(1));
+        auto carry = epi.prologue(pre, t, g);
+        int j = 0;
+        if constexpr (STEADY) {
+            for (; j + 3 < nblk; j += 2) {
+                compute(wa, xa, kof(j));
+                load(wa, xa, kof(j + 2));
+                compute(wb, xb, kof(j + 1));
+                load(wb, xb, kof(j + 3));
+            }
         }
-    }
+        // at most three blocks left: j in wa, j + 1 in wb, j + 2 still to fetch
+        if (j < nblk) compute(wa, xa, kof(j));
+        if (j + 2 < nblk) load(wa, xa, kof(j + 2));
+        if (j + 1 < nblk) compute(wb, xb, kof(j + 1));
+        if (j + 2 < nblk) compute(wa, xa, kof(j + 2));
+        return carry;
+    };
+    auto carry = nblk >= 4 ? stream(std::true_type{}) : stream(std::false_type{});
 
     // ---- finish: KW == 1 keeps everything in registers; otherwise meet in LDS and share the tiles out
     epi.before_barrier(carry, t, g);
