@@ -126,14 +126,37 @@ int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int 
 // ---------------------------------------------------------------------------
 struct Cand { float v; int id; };
 __device__ __forceinline__ bool better(float v, int id, float w, int jd) { return v > w || (v == w && id < jd); }
+
+// Monotone 32-bit key of a float: a > b <=> key(a) > key(b).  -0 shares the key of +0 (they compare equal, so the
+// token id decides between them) and a NaN gets the key of -infinity (it never wins, as with float comparisons).
+__device__ __forceinline__ uint32_t order_key(float v) {
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7fffffffu) > 0x7f800000u) b = 0xff800000u;
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k) { return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k); }
+
+// Wave-wide max / min of a 32-bit unsigned value, the same in every lane: four cross-lane steps inside each row of
+// 16 lanes (swap neighbours, swap pairs, mirror halves of 8, mirror the row), then the four rows meet in scalars.
+template <bool MAX>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t x) {
+    auto op = [](uint32_t a, uint32_t b) { return MAX ? (a > b ? a : b) : (a < b ? a : b); };
+    x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xf, 0xf, false));   // row_half_mirror
+    x = op(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xf, 0xf, false));   // row_mirror
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), r1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), r3 = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    return op(op(r0, r1), op(r2, r3));
+}
+
+// best candidate of the wave in the (value descending, id ascending) order; every lane must be active
 __device__ __forceinline__ Cand wave_best(Cand c) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float w = __shfl_xor(c.v, o, 64);
-        const int jd = __shfl_xor(c.id, o, 64);
-        if (better(w, jd, c.v, c.id)) { c.v = w; c.id = jd; }
-    }
-    return c;
+    const uint32_t key = order_key(c.v);
+    const uint32_t kmax = wave_reduce_u32<true>(key);
+    const uint32_t idmin = wave_reduce_u32<false>(key == kmax ? (uint32_t)c.id : 0xffffffffu);
+    return Cand{key_value(kmax), (int)idmin};
 }
 
 enum { TOPK_THREADS = 1024, TOPK_PER_LANE = 32 };

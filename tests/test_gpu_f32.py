@@ -187,6 +187,45 @@ def test_draft_tree_matches_oracle(tree_name, B, mlp):
     assert sess.main.read_flags() == 0
 
 
+@pytest.mark.parametrize("fp16_family", [False, True])
+def test_draft_tree_exact_ties_take_the_lowest_ids(fp16_family):
+    """Equal logits (duplicated rows of the first head's output matrix, also with a zero row whose logit is +0 or -0
+    against an exactly cancelling one) must come out in ascending token id, in every storage family."""
+    cfg = f32_shape(V=2100) if not fp16_family else f32_shape(V=2100, F=256).with_(dtype="bf16")
+    W = make_weights(cfg, std=0.1)
+    parent = star_tree(9)                                  # the root expands into its 8 most likely tokens
+    tree = O.Tree(parent)
+    m0 = oracle_model(cfg, W)
+    h = np.random.default_rng(11).standard_normal((1, cfg.d)).astype(np.float32)
+    root = uniform_tokens(11, 0, 1, cfg.V)
+    tok0, _ = O.draft_tree(m0, tree, h[0].astype(np.float64), int(root[0]))
+    best, third = tok0[1], tok0[3]
+    wout = W["heads.1.wout"].clone()
+    for dst in (2099, 1030, 1):                            # three more copies of the most likely token's row, ids on both sides
+        if dst != best:
+            wout[dst] = wout[best]
+    for dst in (2000, 70):                                 # and two of the third one's
+        if dst not in (best, third):
+            wout[dst] = wout[third]
+    W = dict(W); W["heads.1.wout"] = wout
+    m = oracle_model(cfg, W)
+    tok, _ = O.draft_tree(m, tree, h[0].astype(np.float64), int(root[0]))
+    kids = tok[1:9]
+    assert sorted(set([1, 1030, 2099, best])) == sorted(kids[:len(set([1, 1030, 2099, best]))]), "the oracle's tie order is not ascending id"
+    sess = gpu_session(cfg, parent, 1, 32, W)
+    sess.h_last.copy_(torch.tensor(h)); sess.root.copy_(root)
+    sess.draft()
+    torch.cuda.synchronize()
+    got = sess.out().tree_tokens.cpu().tolist()[0]
+    print("oracle", kids, "gpu", got[1:9], flush=True)
+    tied_top = len(set([1, 1030, 2099, best]))
+    assert got[1:1 + tied_top] == kids[:tied_top]
+    # the copies of the third token's row are equal among themselves too: wherever they land, ids ascend
+    grp = [t for t in got[1:9] if t in (third, 2000, 70)]
+    assert grp == sorted(grp) and len(grp) >= 1
+    assert sess.main.read_flags() == 0
+
+
 @pytest.mark.parametrize("tree_name,B,L", [("tiny16", 1, 37), ("tiny16", 2, 16), ("random33", 2, 5), ("single", 1, 9), ("chain7", 3, 0)])
 def test_tree_verify_forward_teacher_forced(tree_name, B, L):
     print("case", tree_name, B, L, flush=True)
