@@ -96,6 +96,11 @@ def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu):
     return t_step, t_draft + t_head + t_verify_s
 
 
+def stage(msg):
+    """one progress line per finished stage, on stderr (stdout carries only the JSON line)"""
+    print(f"bench.py: {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,9 +143,11 @@ def main():
     max_len = L0 + (args.steps + args.warmup + 8 + 3 * 40) * (cfg.K + 1) + 2 * cfg.T
     sess = Session(cfg, parent, B, max_len, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=128,
                    want_logits=args.typical)
+    stage("weights packed on the device")
     prompts = torch.stack([uniform_tokens(cfg.seed, b, L0, cfg.V) for b in range(B)])
     sess.prefill(prompts)
     torch.cuda.synchronize()
+    stage("prompt prefilled")
 
     o = sess.out()
     acc_log = torch.zeros(args.steps, B, dtype=torch.int32, device=dev)
@@ -156,6 +163,7 @@ def main():
     dt = time.perf_counter() - t0
     tokens = int(acc_log.sum().item())
     flags = sess.main.read_flags()
+    stage(f"{args.steps} timed steps done")
     L_end = sess.sync_len()
 
     # per-call latencies at the end-of-run context length (seq_len restored after each step)
@@ -196,6 +204,7 @@ def main():
         sess.verify()
     n_launch, ms_sum, w_bytes = sess.main.profile_end()
     restore(saved)
+    stage("per-call timings done")
     peak = 8000.0
     ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
     traffic = read_traffic(args.config)
@@ -275,6 +284,7 @@ def main():
                      "achieved_net_of_empty_bracket": (w_bytes / n_launch) / max((ms_sum / n_launch * 1e3 - empty_bracket_us) * 1e-6, 1e-9) / 1e9 if n_launch else 0.0,
                      "scope": "the 129 GEMM launches of one tree_verify_forward (4 per layer + LM head), averaged over 8 calls"},
     }
+    stage("injected-acceptance points done")
     if not args.no_cpu_baseline:
         ns = min(2, cfg.NL)
         cores = os.cpu_count() or 1

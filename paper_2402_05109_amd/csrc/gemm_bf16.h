@@ -36,6 +36,7 @@
 #pragma once
 
 #include <type_traits>
+#include <utility>
 
 #include "device_common.h"
 
@@ -61,7 +62,14 @@ enum { GEMM_LDS_ROWSUM = 0, GEMM_LDS_ROWINFO = 8 * 128, GEMM_LDS_STAGE = 8 * 128
        GEMM_LDS_SCRATCH = 8 * 128 + 3 * 128 + 8 * (256 + 128) };
 
 // prefetch distance in k-steps: two register sets of U*(NT+MB) KiB per wave
-template <int MB, int NT> struct GemmU { enum { value = (MB * NT >= 6) ? 4 : ((MB + NT >= 6) ? 2 : 4) }; };
+template <int MB, int NT> struct GemmU { enum { value = (MB * NT >= 6) ? 4 : ((MB + NT >= 5) ? 2 : 4) }; };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a compile-time constant
+// whatever the unroller decides, so that register arrays indexed by it never have to live in memory
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 template <int MB, int NT>
 struct GemmTile {
@@ -174,15 +182,15 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
         if (!live) return;
         epi.begin(t, g);
         if constexpr (Epilogue::PAIRED) {
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
+            static_for<MB>([&](auto A) {
+                static_for<4>([&](auto Q4) {
+                    constexpr int a = decltype(A)::value, q4 = decltype(Q4)::value;
                     float x0[4], x1[4];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) { x0[q] = acc[a][0][4 * q4 + q]; x1[q] = acc[a][NT - 1][4 * q4 + q]; }
                     epi.pair4(x0, x1, a, 4 * q4, t, g);
-                }
+                });
+            });
         } else {
 #pragma unroll
             for (int a = 0; a < MB; ++a)
