@@ -188,6 +188,44 @@ def test_draft_tree_matches_oracle(tree_name, B, mlp):
 
 
 @pytest.mark.parametrize("fp16_family", [False, True])
+def test_draft_tree_vocabulary_beyond_the_register_top_k(fp16_family):
+    """V = 33010 > 32768: the top-k that keeps a row in registers does not apply and the scanning kernel runs."""
+    cfg = f32_shape(V=33010) if not fp16_family else f32_shape(V=33010, F=256).with_(dtype="bf16")
+    tol = TOL if not fp16_family else 2e-2
+    W = make_weights(cfg, std=0.1)
+    parent = frozen_tree("tiny16")
+    tree = O.Tree(parent)
+    m = oracle_model(cfg, W)
+    B = 2
+    sess = gpu_session(cfg, parent, B, 32, W)
+    h = np.random.default_rng(21).standard_normal((B, cfg.d)).astype(np.float32)
+    roots = uniform_tokens(21, 0, B, cfg.V)
+    sess.h_last.copy_(torch.tensor(h)); sess.root.copy_(roots)
+    sess.draft()
+    torch.cuda.synchronize()
+    got = sess.out().tree_tokens.cpu().tolist()
+    exact = audited = 0
+    for b in range(B):
+        tok, _ = O.draft_tree(m, tree, h[b].astype(np.float64), int(roots[b]))
+        if got[b] == tok:
+            exact += 1
+            continue
+        _, lg = O.draft_tree(m, tree, h[b].astype(np.float64), int(roots[b]), forced_tokens=got[b])
+        for n, logits in lg.items():
+            kids = [got[b][c] for c in tree.children[n]]
+            ref = O.top_k_ids(logits, len(kids))
+            if kids != ref:
+                audited += 1
+                t = tol * np.max(np.abs(logits))
+                vals = logits[kids]
+                assert np.all(np.diff(vals) <= t) and vals[-1] >= logits[ref[-1]] - t and len(set(kids)) == len(kids)
+    print("rows exact:", exact, "nodes with near-tie reorderings:", audited, flush=True)
+    assert exact >= 1 or fp16_family
+    assert all(0 <= t < cfg.V for row in got for t in row)
+    assert sess.main.read_flags() == 0
+
+
+@pytest.mark.parametrize("fp16_family", [False, True])
 def test_draft_tree_exact_ties_take_the_lowest_ids(fp16_family):
     """Equal logits (duplicated rows of the first head's output matrix, also with a zero row whose logit is +0 or -0
     against an exactly cancelling one) must come out in ascending token id, in every storage family."""
