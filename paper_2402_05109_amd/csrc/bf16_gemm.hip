@@ -380,7 +380,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     const bool may_split = kind == GEMM_KIND_PLAIN;
     p.nw = 1;
     // bands per wave: accumulators MB*NT*16 plus two prefetch sets must fit the register file
-    int nt_max = (p.mb == 4 || pairs) ? 2 : 4;
+    int nt_max = pairs ? 2 : (p.mb == 4 ? 3 : 4);
     int best_nt = pairs ? 2 : 1, best_s = 1;
     double best_cost = 1e30;
     for (int nt = pairs ? 2 : 1; nt <= nt_max; nt += pairs ? 2 : 1) {
@@ -406,7 +406,9 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     if (p.kw == 8 && p.splits > 1 && KT / (8 * p.splits) >= 16) p.kw = 4;   // split K with long runs left: four waves with twice the run each measured faster
     while (p.kw > 1 && KT / (p.kw * p.splits) < 4) p.kw >>= 1;
     while (p.kw > 1 && ((size_t)GEMM_LDS_SCRATCH + (size_t)p.kw * p.mb * p.nt * 16 * 64) * 4 > 150 * 1024) p.kw >>= 1;   // LDS: KW accumulator copies
-    if (mgroups >= 2 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }            // large batch: share X between two N-waves
+    // Two band groups per workgroup only pay for many row groups (measured: slower at 2-4 row groups of 128 rows,
+    // faster at 8): the X tiles both groups read count against the CU's request path even when they hit in L1.
+    if (mgroups >= 6 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }
     p.kpw = ceil_div(KT, p.kw * p.splits);
     return p;
 }
@@ -456,6 +458,7 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
             case 24: launch_one<2, 4>(grid, block, lds, s, g, epi); break;
             case 41: launch_one<4, 1>(grid, block, lds, s, g, epi); break;
             case 42: launch_one<4, 2>(grid, block, lds, s, g, epi); break;
+            case 43: launch_one<4, 3>(grid, block, lds, s, g, epi); break;
             default: return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
         }
     }
