@@ -139,11 +139,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     // k-blocks of U steps are visited in an order rotated by the workgroup index, so that the
     // workgroups streaming different bands do not all ask the L2 for the same X lines at once
     const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
-#ifndef GEMM_EXP_NO_ROTATE
     const int rot = nblk > 0 ? (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk) : 0;
-#else
-    const int rot = 0;
-#endif
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
     // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
     // unconditional: only then can the compiler count how many loads are younger than the set it is about to
