@@ -62,7 +62,9 @@ enum { GEMM_LDS_ROWSUM = 0, GEMM_LDS_ROWINFO = 8 * 128, GEMM_LDS_STAGE = 8 * 128
        GEMM_LDS_SCRATCH = 8 * 128 + 3 * 128 + 8 * (256 + 128) };
 
 // prefetch distance in k-steps: two register sets of U*(NT+MB) KiB per wave
-template <int MB, int NT> struct GemmU { enum { value = (MB * NT >= 12) ? 2 : (MB * NT >= 6) ? 4 : ((MB + NT >= 5) ? 2 : 4) }; };
+template <int MB, int NT> struct GemmU {
+    enum { value = (MB * NT >= 12) ? 2 : (MB * NT == 8) ? 4 : (MB * NT >= 6) ? 2 : ((MB + NT >= 5) ? 2 : 4) };
+};
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a compile-time constant
 // whatever the unroller decides, so that register arrays indexed by it never have to live in memory
