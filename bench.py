@@ -115,6 +115,8 @@ def main():
     ap.add_argument("--typical", action="store_true",
                     help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-injected", action="store_true",
+                    help="skip the injected-acceptance points (for counter-collection runs, where every launch is slow)")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -229,7 +231,7 @@ def main():
         chain.append(kids[chain[-1]])
     sess.sync_len()
     for a in sorted({2, 3, len(chain)}):
-        if a > len(chain) or sess.host_len + 40 * a + cfg.T + 8 > max_len:
+        if args.no_injected or a > len(chain) or sess.host_len + 40 * a + cfg.T + 8 > max_len:
             continue
         src = torch.tensor(chain[1:a], dtype=torch.long, device=dev)
         dst = torch.tensor(chain[:a - 1], dtype=torch.long, device=dev)
@@ -253,6 +255,7 @@ def main():
         t = (time.perf_counter() - t0) / n_steps
         injected.append({"accept_len": a, "ms_per_step": t * 1e3, "tokens_per_s": a * B / t, "n_acc_check": int(o.n_acc[0])})
         sess.sync_len()
+        stage(f"injected acceptance length {a} done")
 
     # autoregressive baseline with the same kernels (one-node tree)
     sess.ctx("ar")
