@@ -167,59 +167,63 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, i
     const int r = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    // the logits first: their addresses need nothing from the tree tables, whose dependent lookups follow
-    float val[TOPK_PER_LANE];
-    uint32_t live = 0;
+    // the logits first: their addresses need nothing from the tree tables, whose dependent lookups follow.
+    // Lane l of the workgroup holds ids l, l + 1024, ...: slot i <-> id i * 1024 + l.  A logit is kept as its
+    // monotone key (order_key); key 0 is below every real key and marks an absent or already extracted entry.
+    uint32_t key[TOPK_PER_LANE];
 #pragma unroll
     for (int i = 0; i < TOPK_PER_LANE; ++i) {
         const int id = i * TOPK_THREADS + threadIdx.x;
-        val[i] = -INFINITY;
-        if (id < V) {
-            val[i] = part_sum(part, S, split_stride, (size_t)r * part_ld + id);
-            live |= 1u << i;
-        }
+        key[i] = id < V ? order_key(part_sum(part, S, split_stride, (size_t)r * part_ld + id)) : 0u;
     }
     const int ne = tree->n_expand[phase];
     const int b = r / ne, j = r - b * ne;
     const int n = tree->expand_nodes[tree->expand_off[phase] + j];
     const int k = tree->n_children[n];
-    __shared__ Cand surv[16 * HYDRA_MAX_TOPK];
+    __shared__ uint32_t surv_key[16 * HYDRA_MAX_TOPK];
+    __shared__ uint32_t surv_id[16 * HYDRA_MAX_TOPK];
     for (int t = 0; t < k; ++t) {
-        Cand c = {-INFINITY, 0x7fffffff};
-        int slot = -1;
+        // the lane's best: the first maximum in slot order is also its lowest id
+        uint32_t bk = 0u, bs = 0u;
 #pragma unroll
-        for (int i = 0; i < TOPK_PER_LANE; ++i) {
-            const int id = i * TOPK_THREADS + threadIdx.x;
-            if (((live >> i) & 1u) && (slot < 0 || better(val[i], id, c.v, c.id))) { c.v = val[i]; c.id = id; slot = i; }
+        for (int i = 0; i < TOPK_PER_LANE; ++i)
+            if (key[i] > bk) { bk = key[i]; bs = (uint32_t)i; }
+        const uint32_t kmax = wave_reduce_u32<true>(bk);
+        const uint32_t idmin = wave_reduce_u32<false>(bk == kmax && kmax != 0u ? bs * TOPK_THREADS + threadIdx.x : 0xffffffffu);
+        if (idmin != 0xffffffffu) {                                   // wave-uniform; the winner's owner retires it
+            const uint32_t slot = idmin / TOPK_THREADS;
+            const bool owner = (idmin % TOPK_THREADS) == threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < TOPK_PER_LANE; ++i)
+                if ((uint32_t)i == slot && owner) key[i] = 0u;
         }
-        const Cand w = wave_best(c);
-        if (slot >= 0 && w.id == c.id) live &= ~(1u << slot);      // the winner's owner retires it
-        if (lane == 0) surv[wave * HYDRA_MAX_TOPK + t] = w;
+        if (lane == 0) { surv_key[wave * HYDRA_MAX_TOPK + t] = kmax; surv_id[wave * HYDRA_MAX_TOPK + t] = idmin; }
     }
     __syncthreads();
     if (wave != 0) return;
-    // 16 * k survivors, k <= 32: lane holds up to 8 of them
-    Cand mine[8];
-    uint32_t mlive = 0;
+    // 16 * k survivors, k <= 32: lane holds up to 8 of them (key 0: a wave that ran out of entries)
+    uint32_t mk[8], mi[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int q = i * 64 + lane;                  // survivor index: wave = q / k, rank = q % k
-        mine[i].v = -INFINITY; mine[i].id = 0x7fffffff;
+        mk[i] = 0u; mi[i] = 0xffffffffu;
         if (q < 16 * k) {
-            mine[i] = surv[(q / k) * HYDRA_MAX_TOPK + (q % k)];
-            if (mine[i].id != 0x7fffffff) mlive |= 1u << i;
+            mk[i] = surv_key[(q / k) * HYDRA_MAX_TOPK + (q % k)];
+            mi[i] = surv_id[(q / k) * HYDRA_MAX_TOPK + (q % k)];
         }
     }
     const int first = tree->first_child[n];
     for (int t = 0; t < k; ++t) {
-        Cand c = {-INFINITY, 0x7fffffff};
-        int slot = -1;
+        uint32_t bk = 0u, bi = 0xffffffffu;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (((mlive >> i) & 1u) && (slot < 0 || better(mine[i].v, mine[i].id, c.v, c.id))) { c = mine[i]; slot = i; }
-        const Cand w = wave_best(c);
-        if (slot >= 0 && w.id == c.id) mlive &= ~(1u << slot);
-        if (lane == 0) tree_tokens[(size_t)b * tree->T + first + t] = w.id;
+            if (mk[i] > bk || (mk[i] == bk && mk[i] != 0u && mi[i] < bi)) { bk = mk[i]; bi = mi[i]; }
+        const uint32_t kmax = wave_reduce_u32<true>(bk);
+        const uint32_t idmin = wave_reduce_u32<false>(bk == kmax && kmax != 0u ? bi : 0xffffffffu);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (mi[i] == idmin) mk[i] = 0u;                           // ids are unique among the survivors
+        if (lane == 0) tree_tokens[(size_t)b * tree->T + first + t] = (int32_t)idmin;
     }
 }
 
