@@ -370,6 +370,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     static const int max_split = (int)env_or("HYDRA_PLAN_MAX_SPLIT", 8);
     GemmPlan p;
     p.splits = 1;
+    p.shared_x = 0;
     p.cost_us = 0.f;
     if (!c->bf16) { p.mb = 1; p.nt = 1; p.nw = 1; p.kw = 1; p.kpw = K; return p; }
     const int mblocks = ceil_div(M, 32);
@@ -410,6 +411,18 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     // faster at 8): the X tiles both groups read count against the CU's request path even when they hit in L1.
     if (mgroups >= 6 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }
     p.kpw = ceil_div(KT, p.kw * p.splits);
+    // Four or more row groups of 128 rows: the X tiles dominate, and enough workgroups remain when 4 or 8 waves take
+    // different band pairs and share X through LDS (gemm_bf16_sharedx_kernel).  No K split in that shape.
+    if (p.mb == 4 && mgroups >= 4 && KT >= 16) {
+        const int groups2 = ceil_div(bands, 2);
+        const int min_wgs = (int)env_or("HYDRA_PLAN_SHARED_X_MIN_WGS", 160.0);    // tests lower it to reach this shape with small models
+        for (int nwt = 8; nwt >= 4; nwt >>= 1) {
+            if (ceil_div(groups2, nwt) * mgroups >= min_wgs) {
+                p.shared_x = nwt; p.nt = 2; p.nw = nwt; p.kw = 1; p.splits = 1; p.kpw = KT;
+                break;
+            }
+        }
+    }
     return p;
 }
 
@@ -430,7 +443,12 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
     g.M = M; g.NTiles = ceil_div(N, 32); g.KT = K / 16; g.kpw = p.kpw; g.NW = p.nw; g.KW = p.kw;
     const int groups = ceil_div(g.NTiles, p.nt);
     dim3 grid(ceil_div(groups, p.nw), p.splits, ceil_div(ceil_div(M, 32), p.mb)), block(p.nw * p.kw * 64);
-    const size_t lds = ((size_t)GEMM_LDS_SCRATCH + (p.kw > 1 ? (size_t)p.kw * p.nw * p.mb * p.nt * 16 * 64 : 0)) * 4;
+    size_t lds = ((size_t)GEMM_LDS_SCRATCH + (p.kw > 1 ? (size_t)p.kw * p.nw * p.mb * p.nt * 16 * 64 : 0)) * 4;
+    if (p.shared_x) {
+        if (p.mb != 4 || p.nt != 2 || p.kw != 1 || p.splits != 1 || p.nw != p.shared_x || (p.shared_x != 4 && p.shared_x != 8))
+            return fail(HYDRA_E_UNSUPPORTED, "gemm: inconsistent shared-X plan");
+        lds = ((size_t)GEMM_LDS_SCRATCH + 2 * 4 * 4 * 256) * 4;          // two blocks of 4 k-steps x 4 row blocks of 1 KiB
+    }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (c->profiling) {
         if (c->ev_used + 2 > c->ev.size())
@@ -439,7 +457,11 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
         HYDRA_HIP(hipEventRecord(e0, s));
     }
     const int key = p.mb * 10 + p.nt;
-    if constexpr (NT_SET == NT_TWO) {
+    if (p.shared_x == 8) {
+        hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, g, epi);
+    } else if (p.shared_x == 4) {
+        hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, g, epi);
+    } else if constexpr (NT_SET == NT_TWO) {
         switch (key) {
             case 12: launch_one<1, 2>(grid, block, lds, s, g, epi); break;
             case 22: launch_one<2, 2>(grid, block, lds, s, g, epi); break;

@@ -240,4 +240,131 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     }
 }
 
+
+// Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
+// pulls through its CU's request path, so here the NWT waves of a workgroup take different band groups, all walk
+// the whole of K block by block in step, and share the X tiles of a block through LDS: each wave fetches 1/NWT of
+// them, two blocks live in LDS, one workgroup barrier per block.  W still goes straight to registers, two sets
+// alternating.  No wave splits K, so the epilogue runs on the wave's own accumulators.
+//   iteration j: multiply block j (X from LDS buffer j % 2) | refill the W set just used with block j + 2 |
+//   barrier (every wave is done with buffer j % 2) | store the fetched X share of block j + 2 there |
+//   request the share of block j + 3.
+// The store becomes visible to the others at the barrier of iteration j + 1, in front of block j + 2.  Every load
+// is unconditional (blocks past the end re-read the last one and their MFMAs are skipped), so waits are exact and
+// every wave meets the same number of barriers.
+template <int MB, int NT, int NWT, class Epilogue, int GEMM_U = 4>
+__global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g, Epilogue epi) {
+    extern __shared__ float red[];                 // [scratch] + 2 x [GEMM_U][MB] X tiles of 1 KiB
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    GemmTile<MB, NT> t;
+    t.tile0 = ((int)blockIdx.x * NWT + wave) * NT;
+    t.mb0 = blockIdx.z * MB;
+    t.lane = lane;
+    t.wave = wave;
+    t.split = 0;
+    t.lds = red;
+    constexpr int XT = GEMM_U * MB;                 // X tiles per block
+    constexpr int XS = (XT + NWT - 1) / NWT;        // of which this wave fetches up to XS
+    u32x4_t *xbuf = reinterpret_cast<u32x4_t *>(red + GEMM_LDS_SCRATCH);
+
+    const u32x4_t *wrow[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) wrow[i] = g.W + (size_t)min(t.tile0 + i, g.NTiles - 1) * g.KT * 64 + lane;
+    const u32x4_t *xbase = g.X + (size_t)t.mb0 * g.KT * 64 + lane;
+    f32x16_t acc[MB][NT];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][i][v] = 0.f;
+
+    const int nblk = (g.KT + GEMM_U - 1) / GEMM_U;
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk);     // the same for all waves of the workgroup
+    auto kof = [&](int j) { if (j >= nblk) return g.KT - 1; int q = j + rot; if (q >= nblk) q -= nblk; return q * GEMM_U; };
+    u32x4_t wa[GEMM_U][NT], wb[GEMM_U][NT], xs[XS];
+    auto load_w = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int k = min(k0 + u, g.KT - 1);
+#pragma unroll
+            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);
+        }
+    };
+    // tile q of a block: k-step q / MB, row block q % MB; this wave fetches q = wave, wave + NWT, ...
+    auto load_x = [&](int k0) {
+#pragma unroll
+        for (int e = 0; e < XS; ++e) {
+            const int q = min(wave + e * NWT, XT - 1);
+            const int k = min(k0 + q / MB, g.KT - 1);
+            xs[e] = xbase[((size_t)(q % MB) * g.KT + k) * 64];
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < XS; ++e) {
+            const int q = wave + e * NWT;
+            if (q < XT) xbuf[((size_t)buf * XT + q) * 64 + lane] = xs[e];
+        }
+    };
+    auto compute = [&](u32x4_t (&w)[GEMM_U][NT], int buf, int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            if (k0 + u < g.KT) {
+#pragma unroll
+                for (int a = 0; a < MB; ++a) {
+                    const u32x4_t x = xbuf[((size_t)buf * XT + u * MB + a) * 64 + lane];
+#pragma unroll
+                    for (int i = 0; i < NT; ++i)
+                        acc[a][i] = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, x), __builtin_bit_cast(a16x8_t, w[u][i]), acc[a][i]);
+                }
+            }
+        }
+    };
+
+    load_w(wa, kof(0));
+    load_x(kof(0));
+    auto pre = epi.issue(t, g);
+    load_w(wb, kof(1));
+    auto carry = epi.prologue(pre, t, g);
+    store_x(0);
+    load_x(kof(1));
+    store_x(1);
+    load_x(kof(2));
+    __syncthreads();
+    for (int j = 0; j < nblk; j += 2) {
+        compute(wa, 0, kof(j));
+        load_w(wa, kof(j + 2));
+        __syncthreads();
+        store_x(0);
+        load_x(kof(j + 3));
+        if (j + 1 < nblk) compute(wb, 1, kof(j + 1));
+        load_w(wb, kof(j + 3));
+        __syncthreads();
+        store_x(1);
+        load_x(kof(j + 4));
+    }
+
+    epi.before_barrier(carry, t, g);
+    if (Epilogue::LDS_PROLOGUE) __syncthreads();
+    if (t.tile0 >= g.NTiles) return;                                // surplus waves streamed a clamped band: discard
+    epi.begin(t, g);
+    if constexpr (Epilogue::PAIRED) {
+        static_for<MB>([&](auto A) {
+            static_for<4>([&](auto Q4) {
+                constexpr int a = decltype(A)::value, q4 = decltype(Q4)::value;
+                float x0[4], x1[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { x0[q] = acc[a][0][4 * q4 + q]; x1[q] = acc[a][NT - 1][4 * q4 + q]; }
+                epi.pair4(x0, x1, a, 4 * q4, t, g);
+            });
+        });
+    } else {
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int i = 0; i < NT; ++i) epi.tile(acc[a][i], a, i, t, g);
+    }
+}
+
 }  // namespace hydra

@@ -43,6 +43,7 @@ struct GemmPlan {      // launch shape of one weight-streaming GEMM (bf16 family
     int nw, kw;        // waves per workgroup along N and along K
     int splits;        // workgroups along K (each writes its own partial output)
     int kpw;           // k-steps (of 16) per wave
+    int shared_x;      // 0, or the number of waves (4 or 8) of the many-rows variant that shares X tiles through LDS
     float cost_us;     // the planner's estimate
 };
 

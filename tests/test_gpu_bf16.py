@@ -188,6 +188,19 @@ def test_draft_tree_matches_oracle(tree_name, B, mlp):
                                             ("prior128", 1, 130), ("chain40", 1, 0), ("random70", 2, 33),
                                             ("prior64", 16, 21), ("prior128", 3, 9)])      # 1024 and 384 rows: several row groups per GEMM
 def test_tree_verify_forward_teacher_forced(tree_name, B, L):
+    _verify_forward_teacher_forced(tree_name, B, L)
+
+
+@pytest.mark.parametrize("min_wgs", [1, 20])
+def test_tree_verify_forward_many_rows_kernel_on_a_small_model(min_wgs, monkeypatch):
+    """1024 rows with the planner's workgroup threshold lowered, so that every GEMM of the small model (residual and
+    plain epilogues included) takes the kernel that shares the X tiles through LDS: eight waves (threshold 1) or
+    four where eight would leave too few workgroups (threshold 20)."""
+    monkeypatch.setenv("HYDRA_PLAN_SHARED_X_MIN_WGS", str(min_wgs))
+    _verify_forward_teacher_forced("prior64", 16, 21)
+
+
+def _verify_forward_teacher_forced(tree_name, B, L):
     print("case", tree_name, B, L, flush=True)
     cfg = bf16_shape()
     W = make_weights(cfg, gain_std=0.1, std=0.05)

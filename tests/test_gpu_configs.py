@@ -1,5 +1,5 @@
 """GPU parity at the widths of the other workload configurations: the 7B shape with
-Hydra++ heads (4-layer MLPs) at batch 4, the 13B shape and the 33B shape.  Each
+Hydra++ heads (4-layer MLPs) at batch 4, 8 and 16, the 13B shape and the 33B shape.  Each
 runs one draft + verify step at full width against the float64 oracle with the
 number of decoder layers (and, for the 33B shape, of draft heads) cut so that the
 oracle needs about ten seconds and a few GB; widths, head counts, FFN sizes,
@@ -26,6 +26,9 @@ CASES = [
     pytest.param(3, dict(NL=2), 4, (301, 17, 256, 90), id="config3-7b-hydra++-batch4"),
     pytest.param(4, dict(NL=1), 1, (523,), id="config4-13b"),
     pytest.param(5, dict(NL=1, K=2), 1, (210,), id="config5-33b"),
+    # 512 and 1024 rows per GEMM: the many-rows kernel that shares the X tiles through LDS (four and eight waves)
+    pytest.param(3, dict(NL=1), 8, (70, 3, 129, 16, 200, 64, 31, 150), id="config3-7b-hydra++-batch8"),
+    pytest.param(3, dict(NL=1), 16, (40, 3, 129, 16, 100, 64, 31, 90, 1, 77, 128, 5, 60, 33, 17, 111), id="config3-7b-hydra++-batch16"),
 ]
 
 
