@@ -138,10 +138,12 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
             }
         }
     };
-    // k-blocks of U steps are visited in an order rotated by the workgroup index, so that the
-    // workgroups streaming different bands do not all ask the L2 for the same X lines at once
+    // k-blocks of U steps are visited in an order rotated by the band-group index, so that the
+    // workgroups streaming different bands do not all ask the L2 for the same X lines at once.  The
+    // workgroups of different row groups that stream the same bands keep the same order: they sit on the
+    // same XCD (the grid's x extent is a multiple of 8 or they are few) and so share each W line in its L2.
     const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
-    const int rot = nblk > 0 ? (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk) : 0;
+    const int rot = nblk > 0 ? (int)((blockIdx.x * 5u) % (unsigned)nblk) : 0;
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
     // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
     // unconditional: only then can the compiler count how many loads are younger than the set it is about to
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
             for (int v = 0; v < 16; ++v) acc[a][i][v] = 0.f;
 
     const int nblk = (g.KT + GEMM_U - 1) / GEMM_U;
-    const int rot = (int)((blockIdx.x * 5u + blockIdx.z) % (unsigned)nblk);     // the same for all waves of the workgroup
+    const int rot = (int)((blockIdx.x * 5u) % (unsigned)nblk);     // the same for all waves of the workgroup and for all row groups
     auto kof = [&](int j) { if (j >= nblk) return g.KT - 1; int q = j + rot; if (q >= nblk) q -= nblk; return q * GEMM_U; };
     u32x4_t wa[GEMM_U][NT], wb[GEMM_U][NT], xs[XS];
     auto load_w = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
@@ -307,17 +309,24 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
             if (q < XT) xbuf[((size_t)buf * XT + q) * 64 + lane] = xs[e];
         }
     };
+    // the X tiles of k-step u + 1 are read from LDS while the MFMAs of k-step u run
     auto compute = [&](u32x4_t (&w)[GEMM_U][NT], int buf, int k0) {
+        const u32x4_t *xb = xbuf + (size_t)buf * XT * 64 + lane;
+        u32x4_t xr[2][MB];
+#pragma unroll
+        for (int a = 0; a < MB; ++a) xr[0][a] = xb[a * 64];
 #pragma unroll
         for (int u = 0; u < GEMM_U; ++u) {
+            if (u + 1 < GEMM_U) {
+#pragma unroll
+                for (int a = 0; a < MB; ++a) xr[(u + 1) & 1][a] = xb[((u + 1) * MB + a) * 64];
+            }
             if (k0 + u < g.KT) {
 #pragma unroll
-                for (int a = 0; a < MB; ++a) {
-                    const u32x4_t x = xbuf[((size_t)buf * XT + u * MB + a) * 64 + lane];
+                for (int a = 0; a < MB; ++a)
 #pragma unroll
                     for (int i = 0; i < NT; ++i)
-                        acc[a][i] = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, x), __builtin_bit_cast(a16x8_t, w[u][i]), acc[a][i]);
-                }
+                        acc[a][i] = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, xr[u & 1][a]), __builtin_bit_cast(a16x8_t, w[u][i]), acc[a][i]);
             }
         }
     };
