@@ -289,7 +289,7 @@ def main():
     }
     stage("injected-acceptance points done")
     if not args.no_cpu_baseline:
-        ns = min(2, cfg.NL)
+        ns = min(8, cfg.NL)
         cores = os.cpu_count() or 1
         try:
             import threadpoolctl
