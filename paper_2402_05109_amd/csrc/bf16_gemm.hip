@@ -79,12 +79,12 @@ __device__ __forceinline__ void rstd_table(float *lds, int lane, int wave, int d
 struct EpiPlain {
     float *out; int ld; size_t split_stride;
     static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
-    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
-    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
-    __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
         float *dst = out + (size_t)t.split * split_stride + (t.tile0 + i) * 32 + (t.lane & 31);
 #pragma unroll
@@ -102,12 +102,12 @@ struct EpiPlain {
 struct EpiResid {
     float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad;
     static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
-    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
-    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
-    __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
         float *__restrict__ xp = x;
         a16_t *__restrict__ xgp = xg;
@@ -146,22 +146,22 @@ struct EpiResid {
 struct EpiSilu {
     const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F;
     static constexpr bool LDS_PROLOGUE = true, PAIRED = false;
-    template <int MB, int NT> __device__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+    template <int MB, int NT> __device__ __forceinline__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         return rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
     }
-    template <int MB, int NT> __device__ NoPre prologue(RowSumRegs r, const GemmTile<MB, NT> &t, const GemmGeom &) const {
+    template <int MB, int NT> __device__ __forceinline__ NoPre prologue(RowSumRegs r, const GemmTile<MB, NT> &t, const GemmGeom &) const {
         rowsum_finish<MB>(r, t.lds, ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave);
         return NoPre{};
     }
-    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
-    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         rstd_table<MB>(t.lds, t.lane, t.wave, dmodel, eps);
     }
     // One band of gate|up columns gives 32 rows x 16 features of the activation: exactly one 1 KiB tile of
     // the next GEMM's input.  The wave assembles it in its LDS staging block and writes it with a single
     // 16-byte-per-lane store (rows past M hold don't-care values in the padded part of the buffer).
     template <int MB, int NT>
-    __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
         const int c = t.lane & 31, hl = t.lane >> 5;
         const bool left = c < 16;
@@ -205,7 +205,7 @@ struct EpiQkvRope {
     const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
     a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
     static constexpr bool LDS_PROLOGUE = true, PAIRED = true;
-    template <int MB, int NT> __device__ QkvRopePre issue(const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    template <int MB, int NT> __device__ __forceinline__ QkvRopePre issue(const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         QkvRopePre p;
         p.rs = rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
         p.max_depth = 0;
@@ -222,7 +222,7 @@ struct EpiQkvRope {
         }
         return p;
     }
-    template <int MB, int NT> __device__ QkvRopeCarry prologue(const QkvRopePre &p, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    template <int MB, int NT> __device__ __forceinline__ QkvRopeCarry prologue(const QkvRopePre &p, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         rowsum_finish<MB>(p.rs, t.lds, ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave);
         QkvRopeCarry c;
 #pragma unroll
@@ -244,7 +244,7 @@ struct EpiQkvRope {
         }
         return c;
     }
-    template <int MB, int NT> __device__ void before_barrier(const QkvRopeCarry &c, const GemmTile<MB, NT> &t, const GemmGeom &) const {
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(const QkvRopeCarry &c, const GemmTile<MB, NT> &t, const GemmGeom &) const {
         if (t.wave != 0) return;
         int *info = reinterpret_cast<int *>(t.lds + GEMM_LDS_ROWINFO);
 #pragma unroll
@@ -253,11 +253,11 @@ struct EpiQkvRope {
             if (r < 32 * MB) { info[r] = c.pos[q]; info[128 + r] = c.pagetok[q]; info[256 + r] = c.bn[q]; }
         }
     }
-    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         rstd_table<MB>(t.lds, t.lane, t.wave, dmodel, eps);
     }
     template <int MB, int NT>
-    __device__ void pair4(const float (&x0)[4], const float (&x1)[4], int a, int v0, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    __device__ __forceinline__ void pair4(const float (&x0)[4], const float (&x1)[4], int a, int v0, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + 1 >= g.NTiles) return;
         const int c = t.lane & 31, hl = t.lane >> 5;
         const int nbs = dmodel >> 5, bph = Dh >> 5, half = Dh >> 1;
@@ -314,19 +314,19 @@ struct EpiQkvRope {
         }
     }
     template <int MB, int NT>
-    __device__ void tile(const f32x16_t &, int, int, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    __device__ __forceinline__ void tile(const f32x16_t &, int, int, const GemmTile<MB, NT> &, const GemmGeom &) const {}
 };
 
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
     const float *bias; float *z; int d; int residual; a16_t *xg;
     static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
-    template <int MB, int NT> __device__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
-    template <int MB, int NT> __device__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
-    template <int MB, int NT> __device__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT>
-    __device__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+    __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         if (t.tile0 + i >= g.NTiles) return;
         const int col = (t.tile0 + i) * 32 + (t.lane & 31);
         const float bv = bias[col];

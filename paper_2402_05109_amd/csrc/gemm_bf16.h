@@ -82,23 +82,34 @@ struct GemmTile {
     float *lds;     // GEMM_LDS_SCRATCH floats of per-workgroup scratch
 };
 
-template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
-__global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
-    extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
+// How the X tiles are fetched.  The default reads them with ordinary loads together with the W tiles.  A gate with
+// DEFERRED_X first requests the two W sets, then calls wait() (all waves of the workgroup, no divergence), and only
+// then reads X, through load_x(): for a workgroup that starts before the kernel part that produces its X is done.
+struct GemmNoGate {
+    static constexpr bool DEFERRED_X = false;
+    __device__ __forceinline__ void wait() const {}
+    static __device__ __forceinline__ u32x4_t load_x(const u32x4_t *p) { return *p; }
+};
+
+// One workgroup of the GEMM: (bx, by, bz) are its band-group, K-split and row-group indices (the plain kernel passes
+// its block indices), red its dynamic LDS.
+template <int MB, int NT, class Epilogue, int GEMM_U, class Gate>
+__device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue &epi, int bx, int by, int bz, float *red,
+                                               const Gate &gate) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nw = wave % g.NW, kw = wave / g.NW;
-    const int group = blockIdx.x * g.NW + nw;       // band group of this wave
+    const int group = bx * g.NW + nw;               // band group of this wave
     GemmTile<MB, NT> t;
     t.tile0 = group * NT;
-    t.mb0 = blockIdx.z * MB;
+    t.mb0 = bz * MB;
     t.lane = lane;
     t.wave = wave;
-    t.split = blockIdx.y;
+    t.split = by;
     t.lds = red;
     float *redbuf = red + GEMM_LDS_SCRATCH;
     // the KW waves of a workgroup share the k-range of their split block by block (wave kw takes the blocks
     // kw, kw + KW, ... of GEMM_U steps), so that together they sweep each band as one contiguous front
-    const int s_begin = min(g.KT, (int)blockIdx.y * g.KW * g.kpw);
+    const int s_begin = min(g.KT, by * g.KW * g.kpw);
     const int k_end = min(g.KT, s_begin + g.KW * g.kpw);
 
     const u32x4_t *wrow[NT];
@@ -123,7 +134,23 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
 #pragma unroll
             for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // used once: streaming load
 #pragma unroll
-            for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
+            for (int a = 0; a < MB; ++a) x[u][a] = Gate::load_x(xrow[a] + (size_t)k * 64);
+        }
+    };
+    auto load_w_only = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int k = min(k0 + u, g.KT - 1);
+#pragma unroll
+            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);
+        }
+    };
+    auto load_x_only = [&](u32x4_t (&x)[GEMM_U][MB], int k0) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int k = min(k0 + u, g.KT - 1);
+#pragma unroll
+            for (int a = 0; a < MB; ++a) x[u][a] = Gate::load_x(xrow[a] + (size_t)k * 64);
         }
     };
     auto compute = [&](u32x4_t (&w)[GEMM_U][NT], u32x4_t (&x)[GEMM_U][MB], int k0) {
@@ -143,7 +170,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     // workgroups of different row groups that stream the same bands keep the same order: they sit on the
     // same XCD (the grid's x extent is a multiple of 8 or they are few) and so share each W line in its L2.
     const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
-    const int rot = nblk > 0 ? (int)((blockIdx.x * 5u) % (unsigned)nblk) : 0;
+    const int rot = nblk > 0 ? (int)(((unsigned)bx * 5u) % (unsigned)nblk) : 0;
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
     // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
     // unconditional: only then can the compiler count how many loads are younger than the set it is about to
@@ -151,10 +178,22 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     // assume the worst, which turns the double buffer into issue-then-wait).
     auto stream = [&](auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
-        if (STEADY || nblk > 0) load(wa, xa, kof(0));
+        if constexpr (Gate::DEFERRED_X) {
+            if (STEADY || nblk > 0) load_w_only(wa, kof(0));
+            if (STEADY || nblk > 1) load_w_only(wb, kof(1));
+        } else {
+            if (STEADY || nblk > 0) load(wa, xa, kof(0));
+        }
         auto pre = epi.issue(t, g);
-        if (STEADY || nblk > 1) load(wb, xb, kof(1));
+        if constexpr (!Gate::DEFERRED_X) {
+            if (STEADY || nblk > 1) load(wb, xb, kof(1));
+        }
         auto carry = epi.prologue(pre, t, g);
+        if constexpr (Gate::DEFERRED_X) {
+            gate.wait();
+            if (STEADY || nblk > 0) load_x_only(xa, kof(0));
+            if (STEADY || nblk > 1) load_x_only(xb, kof(1));
+        }
         int j = 0;
         if constexpr (STEADY) {
             for (; j + 3 < nblk; j += 2) {
@@ -192,10 +231,11 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
                 });
             });
         } else {
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int i = 0; i < NT; ++i) epi.tile(acc[a][i], a, i, t, g);
+            static_for<MB * NT>([&](auto J) {
+                constexpr int a = decltype(J)::value / NT, i = decltype(J)::value % NT;
+                const f32x16_t tile_acc = acc[a][i];                    // a copy: no address of an accumulator escapes
+                epi.tile(tile_acc, a, i, t, g);
+            });
         }
         return;
     }
@@ -242,6 +282,12 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     }
 }
 
+
+template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
+__global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
+    extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
+    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, red, GemmNoGate{});
+}
 
 // Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
 // pulls through its CU's request path, so here the NWT waves of a workgroup take different band groups, all walk
