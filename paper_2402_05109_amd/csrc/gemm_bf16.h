@@ -82,20 +82,10 @@ struct GemmTile {
     float *lds;     // GEMM_LDS_SCRATCH floats of per-workgroup scratch
 };
 
-// How the X tiles are fetched.  The default reads them with ordinary loads together with the W tiles.  A gate with
-// DEFERRED_X first requests the two W sets, then calls wait() (all waves of the workgroup, no divergence), and only
-// then reads X, through load_x(): for a workgroup that starts before the kernel part that produces its X is done.
-struct GemmNoGate {
-    static constexpr bool DEFERRED_X = false;
-    __device__ __forceinline__ void wait() const {}
-    static __device__ __forceinline__ u32x4_t load_x(const u32x4_t *p) { return *p; }
-};
-
 // One workgroup of the GEMM: (bx, by, bz) are its band-group, K-split and row-group indices (the plain kernel passes
 // its block indices), red its dynamic LDS.
-template <int MB, int NT, class Epilogue, int GEMM_U, class Gate>
-__device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue &epi, int bx, int by, int bz, float *red,
-                                               const Gate &gate) {
+template <int MB, int NT, class Epilogue, int GEMM_U>
+__device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue &epi, int bx, int by, int bz, float *red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nw = wave % g.NW, kw = wave / g.NW;
     const int group = bx * g.NW + nw;               // band group of this wave
@@ -134,23 +124,7 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
 #pragma unroll
             for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // used once: streaming load
 #pragma unroll
-            for (int a = 0; a < MB; ++a) x[u][a] = Gate::load_x(xrow[a] + (size_t)k * 64);
-        }
-    };
-    auto load_w_only = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
-#pragma unroll
-        for (int u = 0; u < GEMM_U; ++u) {
-            const int k = min(k0 + u, g.KT - 1);
-#pragma unroll
-            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);
-        }
-    };
-    auto load_x_only = [&](u32x4_t (&x)[GEMM_U][MB], int k0) {
-#pragma unroll
-        for (int u = 0; u < GEMM_U; ++u) {
-            const int k = min(k0 + u, g.KT - 1);
-#pragma unroll
-            for (int a = 0; a < MB; ++a) x[u][a] = Gate::load_x(xrow[a] + (size_t)k * 64);
+            for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
         }
     };
     auto compute = [&](u32x4_t (&w)[GEMM_U][NT], u32x4_t (&x)[GEMM_U][MB], int k0) {
@@ -178,22 +152,10 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
     // assume the worst, which turns the double buffer into issue-then-wait).
     auto stream = [&](auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
-        if constexpr (Gate::DEFERRED_X) {
-            if (STEADY || nblk > 0) load_w_only(wa, kof(0));
-            if (STEADY || nblk > 1) load_w_only(wb, kof(1));
-        } else {
-            if (STEADY || nblk > 0) load(wa, xa, kof(0));
-        }
+        if (STEADY || nblk > 0) load(wa, xa, kof(0));
         auto pre = epi.issue(t, g);
-        if constexpr (!Gate::DEFERRED_X) {
-            if (STEADY || nblk > 1) load(wb, xb, kof(1));
-        }
+        if (STEADY || nblk > 1) load(wb, xb, kof(1));
         auto carry = epi.prologue(pre, t, g);
-        if constexpr (Gate::DEFERRED_X) {
-            gate.wait();
-            if (STEADY || nblk > 0) load_x_only(xa, kof(0));
-            if (STEADY || nblk > 1) load_x_only(xb, kof(1));
-        }
         int j = 0;
         if constexpr (STEADY) {
             for (; j + 3 < nblk; j += 2) {
@@ -286,7 +248,7 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
 template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
 __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
     extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
-    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, red, GemmNoGate{});
+    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, red);
 }
 
 // Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
