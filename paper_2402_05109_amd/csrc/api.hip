@@ -18,7 +18,6 @@ int hip_fail(hipError_t e, const char *what) {
     return HYDRA_E_HIP;
 }
 
-enum { FLAGS_OFF_IN_SLOT = 8000 };
 
 static size_t matrix_bytes(const hydra_ctx *c, size_t N, size_t K) {
     const size_t rows = c->bf16 ? (N + 31) / 32 * 32 : N;
@@ -91,7 +90,12 @@ static int build_tree(const hydra_tree_desc *t, TreeDev *out, std::string *why) 
         out->expand_off[i] = off;
         int cnt = 0;
         for (int n = 0; n < T; ++n)
-            if (out->depth[n] == i - 1 && out->n_children[n] > 0) { out->expand_nodes[off++] = (int16_t)n; ++cnt; }
+            if (out->depth[n] == i - 1 && out->n_children[n] > 0) {
+                out->expand_k[off] = out->n_children[n];
+                out->expand_first[off] = out->first_child[n];
+                out->expand_nodes[off++] = (int16_t)n;
+                ++cnt;
+            }
         out->n_expand[i] = cnt;
     }
     return HYDRA_OK;
@@ -137,6 +141,7 @@ WsLayout ws_layout(const hydra_ctx *c, int B) {
     w.apart = off; off += c->bf16 ? align_up((size_t)B * c->m.n_heads * w.attn_units * rec * 4, 256) : 256;
     w.z = off;     off += align_up(std::max<size_t>(Md, 1) * d * 4, 256);
     w.ss = off;    off += align_up((d / 32 + 1) * rows * 4, 256);
+    w.topk = off;  off += align_up(topk_scratch_bytes(c, (int)std::max<size_t>(Md, 1)), 256);
     w.total = off;
     return w;
 }
@@ -386,7 +391,7 @@ int hydra_draft_tree(hydra_ctx *c, void *stream, int B, void *ws, const float *h
         }
         if ((rc = launch_gemm(c, s, cur, A + c->head[i].wout, part, Mi, V, d, &p))) return rc;
         const size_t sv = (size_t)align_up(Mi, 32) * gemm_npad(c, V);
-        if ((rc = launch_topk(c, s, part, p.splits, gemm_npad(c, V), sv, B, i, tree_tokens))) return rc;
+        if ((rc = launch_topk(c, s, part, p.splits, gemm_npad(c, V), sv, B, i, tree_tokens, W + w.topk))) return rc;
     }
     return HYDRA_OK;
 }

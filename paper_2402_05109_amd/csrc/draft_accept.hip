@@ -159,29 +159,28 @@ __device__ __forceinline__ Cand wave_best(Cand c) {
     return Cand{key_value(kmax), (int)idmin};
 }
 
-enum { TOPK_THREADS = 1024, TOPK_PER_LANE = 32 };
+// Top-k of a logits row in two kernels.  One workgroup on 32000 logits is bound by its own instruction issue (every
+// wave rescans its registers once per extracted entry, and the waves of a workgroup share four SIMDs), so the row is
+// cut into chunks of 1024 ids, one single-wave workgroup each, spread over the chip: lane l holds ids
+// base + l, base + 64 + l, ... as monotone keys (order_key; key 0 is below every real key and marks an absent or
+// already extracted entry), and k rounds leave the chunk's k best, in order, as (key, id) pairs.  The second kernel,
+// one wave per row, picks the k best of those at most 32 * k survivors in the same (value descending, id
+// ascending) order.
+enum { TOPK_CHUNK = 1024, TOPK_PER_LANE = 16, TOPK_MAX_CHUNKS = 32 };
 
-__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, int S, int part_ld, size_t split_stride,
-                                                             int V, const TreeDev *tree, int phase,
-                                                             int32_t *tree_tokens) {
-    const int r = blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-    // the logits first: their addresses need nothing from the tree tables, whose dependent lookups follow.
-    // Lane l of the workgroup holds ids l, l + 1024, ...: slot i <-> id i * 1024 + l.  A logit is kept as its
-    // monotone key (order_key); key 0 is below every real key and marks an absent or already extracted entry.
+__global__ __launch_bounds__(64) void topk_chunk_kernel(const float *part, int S, int part_ld, size_t split_stride, int V,
+                                                         const TreeDev *tree, int ne, int expand_off, uint2 *surv) {
+    const int r = blockIdx.y, chunk = blockIdx.x, lane = threadIdx.x;
+    const int base = chunk * TOPK_CHUNK;
+    // the logits first: their addresses need nothing from the tree tables, whose dependent lookups follow
     uint32_t key[TOPK_PER_LANE];
 #pragma unroll
     for (int i = 0; i < TOPK_PER_LANE; ++i) {
-        const int id = i * TOPK_THREADS + threadIdx.x;
+        const int id = base + i * 64 + lane;
         key[i] = id < V ? order_key(part_sum(part, S, split_stride, (size_t)r * part_ld + id)) : 0u;
     }
-    const int ne = tree->n_expand[phase];
-    const int b = r / ne, j = r - b * ne;
-    const int n = tree->expand_nodes[tree->expand_off[phase] + j];
-    const int k = tree->n_children[n];
-    __shared__ uint32_t surv_key[16 * HYDRA_MAX_TOPK];
-    __shared__ uint32_t surv_id[16 * HYDRA_MAX_TOPK];
+    const int k = tree->expand_k[expand_off + r % ne];
+    uint2 *out = surv + ((size_t)r * gridDim.x + chunk) * HYDRA_MAX_TOPK;
     for (int t = 0; t < k; ++t) {
         // the lane's best: the first maximum in slot order is also its lowest id
         uint32_t bk = 0u, bs = 0u;
@@ -189,39 +188,46 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *part, i
         for (int i = 0; i < TOPK_PER_LANE; ++i)
             if (key[i] > bk) { bk = key[i]; bs = (uint32_t)i; }
         const uint32_t kmax = wave_reduce_u32<true>(bk);
-        const uint32_t idmin = wave_reduce_u32<false>(bk == kmax && kmax != 0u ? bs * TOPK_THREADS + threadIdx.x : 0xffffffffu);
+        const uint32_t idmin = wave_reduce_u32<false>(bk == kmax && kmax != 0u ? (uint32_t)base + bs * 64u + (uint32_t)lane : 0xffffffffu);
         if (idmin != 0xffffffffu) {                                   // wave-uniform; the winner's owner retires it
-            const uint32_t slot = idmin / TOPK_THREADS;
-            const bool owner = (idmin % TOPK_THREADS) == threadIdx.x;
+            const uint32_t off = idmin - (uint32_t)base;
+            const uint32_t slot = off >> 6;
+            const bool owner = (off & 63u) == (uint32_t)lane;
 #pragma unroll
             for (int i = 0; i < TOPK_PER_LANE; ++i)
                 if ((uint32_t)i == slot && owner) key[i] = 0u;
         }
-        if (lane == 0) { surv_key[wave * HYDRA_MAX_TOPK + t] = kmax; surv_id[wave * HYDRA_MAX_TOPK + t] = idmin; }
+        if (lane == 0) out[t] = make_uint2(kmax, idmin);              // key 0: the chunk ran out of entries
     }
-    __syncthreads();
-    if (wave != 0) return;
-    // 16 * k survivors, k <= 32: lane holds up to 8 of them (key 0: a wave that ran out of entries)
-    uint32_t mk[8], mi[8];
+}
+
+__global__ __launch_bounds__(64) void topk_merge_kernel(const uint2 *surv, int chunks, const TreeDev *tree, int ne,
+                                                         int expand_off, int32_t *tree_tokens) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    const int b = r / ne, j = r - b * ne;
+    const int k = tree->expand_k[expand_off + j];
+    const int first = tree->expand_first[expand_off + j];
+    const uint2 *in = surv + (size_t)r * chunks * HYDRA_MAX_TOPK;
+    // chunks * k survivors, at most 32 * 32: lane holds up to 16 of them
+    uint32_t mk[16], mi[16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int q = i * 64 + lane;                  // survivor index: wave = q / k, rank = q % k
+    for (int i = 0; i < 16; ++i) {
+        const int q = i * 64 + lane;                  // survivor index: chunk = q / k, rank = q % k
         mk[i] = 0u; mi[i] = 0xffffffffu;
-        if (q < 16 * k) {
-            mk[i] = surv_key[(q / k) * HYDRA_MAX_TOPK + (q % k)];
-            mi[i] = surv_id[(q / k) * HYDRA_MAX_TOPK + (q % k)];
+        if (q < chunks * k) {
+            const uint2 e = in[(size_t)(q / k) * HYDRA_MAX_TOPK + (q % k)];
+            mk[i] = e.x; mi[i] = e.y;
         }
     }
-    const int first = tree->first_child[n];
     for (int t = 0; t < k; ++t) {
         uint32_t bk = 0u, bi = 0xffffffffu;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 16; ++i)
             if (mk[i] > bk || (mk[i] == bk && mk[i] != 0u && mi[i] < bi)) { bk = mk[i]; bi = mi[i]; }
         const uint32_t kmax = wave_reduce_u32<true>(bk);
         const uint32_t idmin = wave_reduce_u32<false>(bk == kmax && kmax != 0u ? bi : 0xffffffffu);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 16; ++i)
             if (mi[i] == idmin) mk[i] = 0u;                           // ids are unique among the survivors
         if (lane == 0) tree_tokens[(size_t)b * tree->T + first + t] = (int32_t)idmin;
     }
@@ -261,14 +267,24 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const float *part, int S
     }
 }
 
+size_t topk_scratch_bytes(const hydra_ctx *c, int rows) {
+    return (size_t)rows * TOPK_MAX_CHUNKS * HYDRA_MAX_TOPK * sizeof(uint2);
+}
+
 int launch_topk(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride, int B,
-                int phase, int32_t *tree_tokens) {
-    const int rows = B * c->tree.n_expand[phase];
-    if (c->m.vocab <= TOPK_THREADS * TOPK_PER_LANE)
-        hipLaunchKernelGGL(topk_kernel, dim3(rows), dim3(TOPK_THREADS), 0, s, part, S, part_ld, split_stride, c->m.vocab, tree_dev(c), phase, tree_tokens);
-    else
+                int phase, int32_t *tree_tokens, void *scratch) {
+    const int ne = c->tree.n_expand[phase], eoff = c->tree.expand_off[phase];
+    const int rows = B * ne;
+    const int chunks = ceil_div(c->m.vocab, TOPK_CHUNK);
+    if (chunks <= TOPK_MAX_CHUNKS) {
+        hipLaunchKernelGGL(topk_chunk_kernel, dim3(chunks, rows), dim3(64), 0, s, part, S, part_ld, split_stride, c->m.vocab, tree_dev(c), ne, eoff, (uint2 *)scratch);
+        HYDRA_LAUNCH_CHECK("topk_chunk_kernel");
+        hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, s, (const uint2 *)scratch, chunks, tree_dev(c), ne, eoff, tree_tokens);
+        HYDRA_LAUNCH_CHECK("topk_merge_kernel");
+    } else {
         hipLaunchKernelGGL(topk_scan_kernel, dim3(rows), dim3(256), 0, s, part, S, part_ld, split_stride, c->m.vocab, tree_dev(c), phase, tree_tokens);
-    HYDRA_LAUNCH_CHECK("topk_kernel");
+        HYDRA_LAUNCH_CHECK("topk_scan_kernel");
+    }
     return HYDRA_OK;
 }
 

@@ -23,6 +23,8 @@ struct TreeDev {
     int32_t n_expand[HYDRA_MAX_T];        // per phase i (index i): nodes of depth i-1 that have children
     int32_t expand_off[HYDRA_MAX_T + 1];  // start of phase i's list in expand_nodes
     int16_t expand_nodes[HYDRA_MAX_T];    // node ids, phase by phase, ascending
+    int16_t expand_k[HYDRA_MAX_T];        // n_children and first_child of expand_nodes[i], so that one lookup serves a row
+    int16_t expand_first[HYDRA_MAX_T];
     int16_t parent[HYDRA_MAX_T];
     int16_t depth[HYDRA_MAX_T];
     int16_t first_child[HYDRA_MAX_T];
@@ -30,8 +32,8 @@ struct TreeDev {
     uint64_t anc[HYDRA_MAX_T][2];         // bit a of anc[n]: a is n or an ancestor of n
 };
 
-enum { TABLE_SLOTS = 16, TABLE_SLOT_BYTES = 8192 };
-static_assert(sizeof(TreeDev) <= TABLE_SLOT_BYTES, "tree table slot too small");
+enum { TABLE_SLOTS = 16, TABLE_SLOT_BYTES = 8192, FLAGS_OFF_IN_SLOT = 8000 };    // a slot: the tree, then (at 8000) the flags word
+static_assert(sizeof(TreeDev) <= FLAGS_OFF_IN_SLOT, "tree table slot too small");
 
 // Offsets (bytes) of everything inside the weight arena.
 struct LayerOff { size_t attn_norm, wqkv, wo, ffn_norm, wgu, wdown; };
@@ -94,7 +96,7 @@ inline int    ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---- workspace ------------------------------------------------------------
 struct WsLayout {
-    size_t flags, x, xa, xb, part, qbuf, apart, z, ss, total;
+    size_t flags, x, xa, xb, part, qbuf, apart, z, ss, topk, total;
     int attn_units;     // split-KV units per (row, head, query group)
 };
 WsLayout ws_layout(const hydra_ctx *c, int B);
@@ -161,7 +163,8 @@ int launch_draft_gather(hydra_ctx *c, hipStream_t s, int B, int phase, const flo
 int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                      const float *bias, float *z, bool residual, void *x_out, int M);
 int launch_topk(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
-                int B, int phase, int32_t *tree_tokens);
+                int B, int phase, int32_t *tree_tokens, void *scratch);
+size_t topk_scratch_bytes(const hydra_ctx *c, int rows);      // bytes of `scratch` for that many logits rows
 // accept / compact
 int launch_accept(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens, const int32_t *argmax,
                   int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
