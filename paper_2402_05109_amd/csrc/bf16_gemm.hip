@@ -3,6 +3,8 @@
 // into its tile order.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "gemm_bf16.h"
 #include "internal.h"
 
@@ -78,7 +80,7 @@ __device__ __forceinline__ void rstd_table(float *lds, int lane, int wave, int d
 // out[split][row][col] = acc
 struct EpiPlain {
     float *out; int ld; size_t split_stride;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
@@ -101,7 +103,7 @@ struct EpiPlain {
 // band's 32 columns of x^2.
 struct EpiResid {
     float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
@@ -145,7 +147,7 @@ struct EpiResid {
 // half rows v >= 8, each fetching the partner value from the lane 16 columns away.
 struct EpiSilu {
     const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F;
-    static constexpr bool LDS_PROLOGUE = true, PAIRED = false;
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         return rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
     }
@@ -204,7 +206,31 @@ struct EpiQkvRope {
     const float *ss; int nb; int Mpad; int dmodel; float eps;
     const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
     a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
-    static constexpr bool LDS_PROLOGUE = true, PAIRED = true;
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = true, EXTRA_BLOCKS = true;
+    // Workgroups behind the last band group (the q|k|v GEMM of up to 64 rows leaves a quarter of the CUs without
+    // one) read this layer's cached K and V pages once, so that tree attention, which follows and is a chain of
+    // dependent round trips, finds them in the memory-side cache.  Nothing is computed from the values.
+    __device__ __forceinline__ void extra_block(int w, int n, const GemmGeom &g) const {
+        const int rows = (g.M + T - 1) / T;
+        const int n16 = H * Dh * 2;                                  // 16-byte pieces of one page of one layer (16 tokens, all heads)
+        uint32_t sink = 0u;
+        for (int b = 0; b < rows; ++b) {
+            const int L = seq_len[b];
+            if (L <= 0 || L + T > max_pages * 16) continue;          // uniform over the workgroup
+            const int pages = (L + 15) >> 4;
+            for (int pi = (w + n - b % n) % n; pi < pages; pi += n) {
+                const int page = page_table[(size_t)b * max_pages + pi];
+                if ((unsigned)page >= (unsigned)n_pages) continue;
+                const u32x4_t *kp = reinterpret_cast<const u32x4_t *>(kpages + kv_block_base(layer, n_pages, page, H, 0, Dh));
+                const u32x4_t *vp = reinterpret_cast<const u32x4_t *>(vpages + kv_block_base(layer, n_pages, page, H, 0, Dh));
+                for (int i = threadIdx.x; i < n16; i += blockDim.x) {
+                    const u32x4_t a = kp[i], c = vp[i];
+                    sink ^= a[0] ^ c[0];
+                }
+            }
+        }
+        asm volatile("" : : "v"(sink));                              // the loads must be issued although nothing uses them
+    }
     template <int MB, int NT> __device__ __forceinline__ QkvRopePre issue(const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         QkvRopePre p;
         p.rs = rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
@@ -320,7 +346,7 @@ struct EpiQkvRope {
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
     const float *bias; float *z; int d; int residual; a16_t *xg;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
@@ -437,12 +463,13 @@ static void launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t s, const G
 enum { NT_ANY = 0, NT_TWO = 2 };
 template <class Epi, int NT_SET>
 static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
-                       const GemmPlan &p, const Epi &epi) {
+                       const GemmPlan &p, const Epi &epi, int extra_blocks = 0) {
     GemmGeom g;
     g.X = (const u32x4_t *)X; g.W = (const u32x4_t *)W;
     g.M = M; g.NTiles = ceil_div(N, 32); g.KT = K / 16; g.kpw = p.kpw; g.NW = p.nw; g.KW = p.kw;
     const int groups = ceil_div(g.NTiles, p.nt);
     dim3 grid(ceil_div(groups, p.nw), p.splits, ceil_div(ceil_div(M, 32), p.mb)), block(p.nw * p.kw * 64);
+    if (Epi::EXTRA_BLOCKS && !p.shared_x && grid.y == 1 && grid.z == 1) grid.x += extra_blocks;    // see Epilogue::extra_block
     size_t lds = ((size_t)GEMM_LDS_SCRATCH + (p.kw > 1 ? (size_t)p.kw * p.nw * p.mb * p.nt * 16 * 64 : 0)) * 4;
     if (p.shared_x) {
         if (p.mb != 4 || p.nt != 2 || p.kw != 1 || p.splits != 1 || p.nw != p.shared_x || (p.shared_x != 4 && p.shared_x != 8))
@@ -580,7 +607,11 @@ int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void 
     EpiQkvRope epi{rs.ss, rs.nb, rs.Mpad, d, rs.eps, seq_len, tree_dev(c), kv->page_table, kv->max_pages, kv->n_pages, layer,
                    (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, rope_dev(c), c->m.n_heads, c->m.head_dim,
                    c->tree.T, c->m.max_pos, flags};
-    return launch_bf16<EpiQkvRope, NT_TWO>(c, s, X, W, M, 3 * d, d, p, epi);
+    // CUs that get no band group pre-read the layer's K/V pages (at most a quarter of the chip, and only when asked to)
+    const int wgs = ceil_div(ceil_div(ceil_div(3 * d, 32), p.nt), p.nw);
+    const int idle = std::min(64, 256 - wgs);
+    const int extra = (idle >= 8 && env_or("HYDRA_KV_TOUCH", 1.0) != 0.0) ? idle : 0;
+    return launch_bf16<EpiQkvRope, NT_TWO>(c, s, X, W, M, 3 * d, d, p, epi, extra);
 }
 
 template <int MB, int NT, class Epi>

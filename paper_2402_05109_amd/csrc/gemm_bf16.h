@@ -248,6 +248,10 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
 template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
 __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
     extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
+    if constexpr (Epilogue::EXTRA_BLOCKS) {        // workgroups behind the last band group: side work of the epilogue's choosing
+        const int wgs = ((g.NTiles + NT - 1) / NT + g.NW - 1) / g.NW;
+        if ((int)blockIdx.x >= wgs) { epi.extra_block((int)blockIdx.x - wgs, (int)gridDim.x - wgs, g); return; }
+    }
     gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, red);
 }
 
