@@ -546,12 +546,17 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, 
     float sq = 0.f;
     if (k < d) {                                              // d % 32 == 0: a group of 8 lanes is all in or all out
         f32x4_t a = *reinterpret_cast<const f32x4_t *>(x + (size_t)m * d + k);
-        for (int sp = 0; sp < S; ++sp) {
-            const f32x4_t q = *reinterpret_cast<const f32x4_t *>(part + (size_t)sp * split_stride + (size_t)m * ld + k);
-            a[0] += q[0]; a[1] += q[1]; a[2] += q[2]; a[3] += q[3];
+        const f32x4_t gn = *reinterpret_cast<const f32x4_t *>(gain + k);
+        const float *src = part + (size_t)m * ld + k;
+        for (int s0 = 0; s0 < S; s0 += 4) {                    // four partials per round trip (surplus loads re-read the last split)
+            f32x4_t q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const f32x4_t *>(src + (size_t)min(s0 + u, S - 1) * split_stride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)                        // added in split order
+                if (s0 + u < S) { a[0] += q[u][0]; a[1] += q[u][1]; a[2] += q[u][2]; a[3] += q[u][3]; }
         }
         *reinterpret_cast<f32x4_t *>(x + (size_t)m * d + k) = a;
-        const f32x4_t gn = *reinterpret_cast<const f32x4_t *>(gain + k);
         const uint32_t lo = f2a_pack(a[0] * gn[0], a[1] * gn[1]);
         const uint32_t hi = f2a_pack(a[2] * gn[2], a[3] * gn[3]);
         uint32_t *dst = reinterpret_cast<uint32_t *>(xg + x_index<true>(m, k, d));     // 4 consecutive k share an 8-run

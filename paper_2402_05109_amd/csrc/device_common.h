@@ -100,9 +100,19 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // sum of S split-K partial results of one output element
+// Four partials per memory round trip: the loads of a group are unconditional (surplus ones re-read the last split), so
+// they are all in flight before the first add; the adds keep the split order.
 __device__ __forceinline__ float part_sum(const float *part, int S, size_t split_stride, size_t idx) {
-    float a = part[idx];
-    for (int s = 1; s < S; ++s) a += part[(size_t)s * split_stride + idx];
+    float a = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 4) {
+        float q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) q[u] = part[(size_t)min(s0 + u, S - 1) * split_stride + idx];
+        a = s0 == 0 ? q[0] : a + q[0];
+#pragma unroll
+        for (int u = 1; u < 4; ++u)
+            if (s0 + u < S) a += q[u];
+    }
     return a;
 }
 
