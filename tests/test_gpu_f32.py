@@ -225,6 +225,44 @@ def test_draft_tree_vocabulary_beyond_the_register_top_k(fp16_family):
     assert sess.main.read_flags() == 0
 
 
+@pytest.mark.parametrize("V", [32768, 31999])
+def test_draft_tree_widest_node_on_the_largest_chunked_vocabulary(V):
+    """The limits of the two-kernel top-k: 32 children per node (HYDRA_MAX_TOPK) and 32 chunks of 1024 ids
+    (V = 32768: the merge kernel's 1024 survivor slots are all in use; V = 31999: a ragged last chunk)."""
+    cfg = f32_shape(V=V)
+    W = make_weights(cfg, std=0.1)
+    parent = star_tree(32) + [1, 1, 2]                     # the root's 32 children, then two nodes that expand again
+    tree = O.Tree(parent)
+    m = oracle_model(cfg, W)
+    B = 2
+    sess = gpu_session(cfg, parent, B, 32, W)
+    h = np.random.default_rng(33).standard_normal((B, cfg.d)).astype(np.float32)
+    roots = uniform_tokens(33, 0, B, cfg.V)
+    sess.h_last.copy_(torch.tensor(h)); sess.root.copy_(roots)
+    sess.draft()
+    torch.cuda.synchronize()
+    got = sess.out().tree_tokens.cpu().tolist()
+    exact = audited = 0
+    for b in range(B):
+        tok, _ = O.draft_tree(m, tree, h[b].astype(np.float64), int(roots[b]))
+        if got[b] == tok:
+            exact += 1
+            continue
+        _, lg = O.draft_tree(m, tree, h[b].astype(np.float64), int(roots[b]), forced_tokens=got[b])
+        for n, logits in lg.items():
+            kids = [got[b][c] for c in tree.children[n]]
+            ref = O.top_k_ids(logits, len(kids))
+            if kids != ref:
+                audited += 1
+                t = TOL * np.max(np.abs(logits))
+                vals = logits[kids]
+                assert np.all(np.diff(vals) <= t) and vals[-1] >= logits[ref[-1]] - t and len(set(kids)) == len(kids)
+    print("rows exact:", exact, "nodes with near-tie reorderings:", audited, flush=True)
+    assert exact >= 1
+    assert all(0 <= t < cfg.V for row in got for t in row)
+    assert sess.main.read_flags() == 0
+
+
 @pytest.mark.parametrize("fp16_family", [False, True])
 def test_draft_tree_exact_ties_take_the_lowest_ids(fp16_family):
     """Equal logits (duplicated rows of the first head's output matrix, also with a zero row whose logit is +0 or -0
