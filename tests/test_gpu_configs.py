@@ -1,5 +1,6 @@
 """GPU parity at the widths of the other workload configurations: the 7B shape with
-Hydra++ heads (4-layer MLPs) at batch 4, 8 and 16, the 13B shape and the 33B shape.  Each
+Hydra++ heads (4-layer MLPs) at batch 4, 8 and 16, the 13B shape (also at its longest prompt,
+4096) and the 33B shape (trees of 32, 64 and 128 nodes, batch 1 and 4).  Each
 runs one draft + verify step at full width against the float64 oracle with the
 number of decoder layers (and, for the 33B shape, of draft heads) cut so that the
 oracle needs about ten seconds and a few GB; widths, head counts, FFN sizes,
@@ -26,6 +27,11 @@ CASES = [
     pytest.param(3, dict(NL=2), 4, (301, 17, 256, 90), id="config3-7b-hydra++-batch4"),
     pytest.param(4, dict(NL=1), 1, (523,), id="config4-13b"),
     pytest.param(5, dict(NL=1, K=2), 1, (210,), id="config5-33b"),
+    # config 5's other tree sizes and its batch of 4 (128 rows per GEMM in both)
+    pytest.param(5, dict(NL=1, K=2, tree="prior128"), 1, (333,), id="config5-33b-tree128"),
+    pytest.param(5, dict(NL=1, K=2, tree="prior32"), 4, (97, 2048, 640, 15), id="config5-33b-tree32-batch4"),
+    # config 4's longest prompt: the keys of a head are split over workgroups and merged, at 40 heads
+    pytest.param(4, dict(NL=1), 1, (4096,), id="config4-13b-context4096"),
     # 512 and 1024 rows per GEMM: the many-rows kernel that shares the X tiles through LDS (four and eight waves)
     pytest.param(3, dict(NL=1), 8, (70, 3, 129, 16, 200, 64, 31, 150), id="config3-7b-hydra++-batch8"),
     pytest.param(3, dict(NL=1), 16, (40, 3, 129, 16, 100, 64, 31, 90, 1, 77, 128, 5, 60, 33, 17, 111), id="config3-7b-hydra++-batch16"),
@@ -35,11 +41,13 @@ CASES = [
 @pytest.mark.parametrize("idx,over,B,lens", CASES)
 def test_draft_and_verify_at_full_width(idx, over, B, lens):
     from paper_2402_05109_amd.session import Session
+    over = dict(over)
+    tree_name = over.pop("tree", "prior64")
     cfg = CONFIGS[idx].with_(**over)
     spec = WeightSpec(cfg, gain_std=0.1)
     dev = "cuda:0"
     W = {n: make_tensor(spec, n, device=dev).cpu() for n in tensor_names(cfg)}
-    parent = frozen_tree("prior64")
+    parent = frozen_tree(tree_name)
     if cfg.K < 4:                                       # fewer heads: cut the tree at depth K
         depth = [0] * len(parent)
         for n in range(1, len(parent)):
