@@ -200,6 +200,34 @@ def test_tree_verify_forward_many_rows_kernel_on_a_small_model(min_wgs, monkeypa
     _verify_forward_teacher_forced("prior64", 16, 21)
 
 
+def test_tree_verify_forward_is_bitwise_the_same_without_the_kv_pre_read(monkeypatch):
+    """The spare workgroups of the q|k|v launch only read cached K/V pages ahead of attention; switching them off
+    must not change a single bit of any output (rows of different lengths, one of them empty)."""
+    cfg = bf16_shape()
+    W = make_weights(cfg, gain_std=0.1, std=0.05)
+    parent = TREES["prior64"]()
+    T = len(parent)
+    B, lens = 3, [150, 0, 37]
+    sess = gpu_session(cfg, parent, B, 200, W, page_perm_seed=3, want_logits=True)
+    rng = np.random.default_rng(8)
+    for l in range(cfg.NL):
+        t = torch.tensor(rng.standard_normal((B, max(lens), 2, cfg.H, cfg.Dh)) * 0.5, dtype=torch.float32, device="cuda:0")
+        sess.main.kv_write(B, l, sess.kv, 0, max(lens), t)
+    o = sess.out()
+    toks = torch.stack([uniform_tokens(8, b, T, cfg.V) for b in range(B)]).to(torch.int32)
+    outs = []
+    for mode in ("1", "0"):
+        monkeypatch.setenv("HYDRA_KV_TOUCH", mode)
+        sess.seq_len.copy_(torch.tensor(lens, dtype=torch.int32)); sess.host_len = max(lens)
+        o.tree_tokens.copy_(toks)
+        sess.verify()
+        torch.cuda.synchronize()
+        assert sess.main.read_flags() == 0
+        outs.append((o.hidden.clone(), o.logits.clone(), o.argmax.clone(), o.margin.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def _verify_forward_teacher_forced(tree_name, B, L):
     print("case", tree_name, B, L, flush=True)
     cfg = bf16_shape()
