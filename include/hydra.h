@@ -296,7 +296,8 @@ int hydra_kv_read(hydra_ctx *ctx, void *stream, int B, int layer, const hydra_kv
 
 /* Per-kernel-family timing with HIP events on `stream` (for benchmarks).
  * hydra_profile_begin switches it on and zeroes the counters; every launch of
- * the weight-streaming GEMM kernel is then bracketed by an event pair.
+ * the weight-streaming GEMM kernel then carries an event pair that takes the
+ * kernel's own begin and end times on its stream.
  * hydra_profile_end synchronises and returns launches, summed milliseconds and
  * summed weight bytes streamed by those launches. */
 int hydra_profile_begin(hydra_ctx *ctx);

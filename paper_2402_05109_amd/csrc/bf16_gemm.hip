@@ -5,6 +5,8 @@
 
 #include <algorithm>
 
+#include <hip/hip_ext.h>
+
 #include "gemm_bf16.h"
 #include "internal.h"
 
@@ -454,10 +456,12 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
 
 int launch_gemm_f32(hydra_ctx *c, hipStream_t s, const float *X, const float *W, float *part, int M, int N, int K);
 
+// e0/e1 non-null (profiling): the events take the kernel's own begin and end times, not the stream's before and after
 template <int MB, int NT, class Epi>
-static void launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t s, const GemmGeom &g, const Epi &epi) {
+static void launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t s, const GemmGeom &g, const Epi &epi, hipEvent_t e0, hipEvent_t e1) {
     constexpr int MAXT = (MB * NT >= 6) ? 256 : 512;
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, g, epi);
+    if (e0) hipExtLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
+    else    hipLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, g, epi);
 }
 
 enum { NT_ANY = 0, NT_TWO = 2 };
@@ -481,39 +485,39 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
         if (c->ev_used + 2 > c->ev.size())
             for (int i = 0; i < 2; ++i) { hipEvent_t e; HYDRA_HIP(hipEventCreate(&e)); c->ev.push_back(e); }
         e0 = c->ev[c->ev_used++]; e1 = c->ev[c->ev_used++];
-        HYDRA_HIP(hipEventRecord(e0, s));
     }
     const int key = p.mb * 10 + p.nt;
     if (p.shared_x == 8) {
-        hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, g, epi);
+        if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
+        else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, g, epi);
     } else if (p.shared_x == 4) {
-        hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, g, epi);
+        if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
+        else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, g, epi);
     } else if constexpr (NT_SET == NT_TWO) {
         switch (key) {
-            case 12: launch_one<1, 2>(grid, block, lds, s, g, epi); break;
-            case 22: launch_one<2, 2>(grid, block, lds, s, g, epi); break;
-            case 42: launch_one<4, 2>(grid, block, lds, s, g, epi); break;
+            case 12: launch_one<1, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 22: launch_one<2, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 42: launch_one<4, 2>(grid, block, lds, s, g, epi, e0, e1); break;
             default: return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
         }
     } else {
         switch (key) {
-            case 11: launch_one<1, 1>(grid, block, lds, s, g, epi); break;
-            case 12: launch_one<1, 2>(grid, block, lds, s, g, epi); break;
-            case 13: launch_one<1, 3>(grid, block, lds, s, g, epi); break;
-            case 14: launch_one<1, 4>(grid, block, lds, s, g, epi); break;
-            case 21: launch_one<2, 1>(grid, block, lds, s, g, epi); break;
-            case 22: launch_one<2, 2>(grid, block, lds, s, g, epi); break;
-            case 23: launch_one<2, 3>(grid, block, lds, s, g, epi); break;
-            case 24: launch_one<2, 4>(grid, block, lds, s, g, epi); break;
-            case 41: launch_one<4, 1>(grid, block, lds, s, g, epi); break;
-            case 42: launch_one<4, 2>(grid, block, lds, s, g, epi); break;
-            case 43: launch_one<4, 3>(grid, block, lds, s, g, epi); break;
+            case 11: launch_one<1, 1>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 12: launch_one<1, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 13: launch_one<1, 3>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 14: launch_one<1, 4>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 21: launch_one<2, 1>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 22: launch_one<2, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 23: launch_one<2, 3>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 24: launch_one<2, 4>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 41: launch_one<4, 1>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 42: launch_one<4, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 43: launch_one<4, 3>(grid, block, lds, s, g, epi, e0, e1); break;
             default: return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
         }
     }
     HYDRA_LAUNCH_CHECK("gemm_bf16_kernel");
     if (c->profiling) {
-        HYDRA_HIP(hipEventRecord(e1, s));
         c->prof_bytes += (double)N * K * 2;
         c->prof_launches += 1;
     }
