@@ -110,6 +110,7 @@ def main():
     ap.add_argument("--tree", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="candidate-tree size (nodes with the root); 0 = the configuration's own (the headline workload)")
     ap.add_argument("--batch", type=int, default=0, help="batch rows (0 = the configuration's first batch size)")
+    ap.add_argument("--prompt", type=int, default=0, help="prompt length (0 = the configuration's first prompt length)")
     ap.add_argument("--medusa", action="store_true",
                     help="Medusa-style draft heads (h_last only, one hidden layer with a skip connection) instead of Hydra heads: the baseline draft cost")
     ap.add_argument("--typical", action="store_true",
@@ -139,7 +140,7 @@ def main():
         cfg = cfg.with_(medusa=1)
     tree_name = {16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T]
     parent = frozen_tree(tree_name)
-    B, L0 = (args.batch or cfg.batch[0]), cfg.prompt[0]
+    B, L0 = (args.batch or cfg.batch[0]), (args.prompt or cfg.prompt[0])
     spec = WeightSpec(cfg)
     dev = "cuda:0"
     max_len = L0 + (args.steps + args.warmup + 8 + 3 * 40) * (cfg.K + 1) + 2 * cfg.T

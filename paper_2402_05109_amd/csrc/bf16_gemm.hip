@@ -208,17 +208,20 @@ struct EpiQkvRope {
     const float *ss; int nb; int Mpad; int dmodel; float eps;
     const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
     a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
+    int kv_touch_max;       // rows with more keys than this are not pre-read (see extra_block)
     static constexpr bool LDS_PROLOGUE = true, PAIRED = true, EXTRA_BLOCKS = true;
     // Workgroups behind the last band group (the q|k|v GEMM of up to 64 rows leaves a quarter of the CUs without
     // one) read this layer's cached K and V pages once, so that tree attention, which follows and is a chain of
-    // dependent round trips, finds them in the memory-side cache.  Nothing is computed from the values.
+    // dependent round trips, finds them in the memory-side cache.  Nothing is computed from the values.  Only for
+    // short rows: with more keys attention is a throughput problem spread over many workgroups, and the extra
+    // pass over K/V costs this GEMM more than attention gains (measured at 2066 and 4114 keys: +0.13 and +0.63 ms).
     __device__ __forceinline__ void extra_block(int w, int n, const GemmGeom &g) const {
         const int rows = (g.M + T - 1) / T;
         const int n16 = H * Dh * 2;                                  // 16-byte pieces of one page of one layer (16 tokens, all heads)
         uint32_t sink = 0u;
         for (int b = 0; b < rows; ++b) {
             const int L = seq_len[b];
-            if (L <= 0 || L + T > max_pages * 16) continue;          // uniform over the workgroup
+            if (L <= 0 || L + T > max_pages * 16 || L + T > kv_touch_max) continue;      // uniform over the workgroup
             const int pages = (L + 15) >> 4;
             for (int pi = (w + n - b % n) % n; pi < pages; pi += n) {
                 const int page = page_table[(size_t)b * max_pages + pi];
@@ -615,11 +618,13 @@ int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void 
     GemmPlan p = plan_gemm(c, M, 3 * d, d, GEMM_KIND_PAIRS);
     EpiQkvRope epi{rs.ss, rs.nb, rs.Mpad, d, rs.eps, seq_len, tree_dev(c), kv->page_table, kv->max_pages, kv->n_pages, layer,
                    (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, rope_dev(c), c->m.n_heads, c->m.head_dim,
-                   c->tree.T, c->m.max_pos, flags};
-    // CUs that get no band group pre-read the layer's K/V pages (at most a quarter of the chip, and only when asked to)
+                   c->tree.T, c->m.max_pos, flags, (int)env_or("HYDRA_KV_TOUCH_MAX_KEYS", 1280.0)};
+    // CUs that get no band group pre-read the layer's K/V pages: only where an eighth of the chip or more is idle
+    // (7B: 64 CUs; measured at the 13B shape, 16 idle CUs: the GEMM is close to the HBM limit there and the pre-read
+    // costs more than attention gains, verify 6.35 -> 6.52 ms)
     const int wgs = ceil_div(ceil_div(ceil_div(3 * d, 32), p.nt), p.nw);
     const int idle = std::min(64, 256 - wgs);
-    const int extra = (idle >= 8 && env_or("HYDRA_KV_TOUCH", 1.0) != 0.0) ? idle : 0;
+    const int extra = (idle >= 32 && env_or("HYDRA_KV_TOUCH", 1.0) != 0.0) ? idle : 0;
     return launch_bf16<EpiQkvRope, NT_TWO>(c, s, X, W, M, 3 * d, d, p, epi, extra);
 }
 
