@@ -234,38 +234,34 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     }
     __syncthreads();
     if (!active) return;
-    // wave kwv finishes bands dt = kwv, kwv + KWV, ...
+    // the (band, group of 4 registers = 4 consecutive dims) items are shared out over the KWV waves of the query tile
     const int query = qtile * 32 + col;
     const bool final_out = key_wgs == 1;
     const float inv = final_out ? 1.0f / l_tot : 1.0f;
     float *rec = apart + ((((size_t)b * H + h) * gridDim.x) + blockIdx.x) * apart_record(Tq, DH);
-    for (int dt = kwv; dt < DT; dt += KWV) {
-        float acc[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int id = kwv; id < DT * 4; id += KWV) {
+        const int dt = id >> 2, g4 = id & 3;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
         for (int w = 0; w < KWV; ++w) {
             const float *src = ob + (size_t)(qw * KWV + w) * DT * 16 * 64 + lane;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] += src[(dt * 16 + v) * 64];
+            for (int q = 0; q < 4; ++q) acc[q] += src[(dt * 16 + 4 * g4 + q) * 64];
         }
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const int dim = 32 * dt + 8 * g4 + 4 * hl;          // 4 consecutive dims: registers 4*g4 .. 4*g4+3
-            if (final_out) {
-                if (query < T) {
-                    const int m = b * T + query;
-                    if (PACKED) {
-                        u32x2_t pk = {f2a_pack(acc[4 * g4] * inv, acc[4 * g4 + 1] * inv), f2a_pack(acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv)};
-                        *reinterpret_cast<u32x2_t *>(reinterpret_cast<a16_t *>(out) + x_index<true>(m, h * DH + dim, H * DH)) = pk;
-                    } else {
-                        f32x4_t v4 = {acc[4 * g4] * inv, acc[4 * g4 + 1] * inv, acc[4 * g4 + 2] * inv, acc[4 * g4 + 3] * inv};
-                        *reinterpret_cast<f32x4_t *>(reinterpret_cast<float *>(out) + ((size_t)m * H + h) * DH + dim) = v4;
-                    }
+        const int dim = 32 * dt + 8 * g4 + 4 * hl;
+        if (final_out) {
+            if (query < T) {
+                const int m = b * T + query;
+                if (PACKED) {
+                    u32x2_t pk = {f2a_pack(acc[0] * inv, acc[1] * inv), f2a_pack(acc[2] * inv, acc[3] * inv)};
+                    *reinterpret_cast<u32x2_t *>(reinterpret_cast<a16_t *>(out) + x_index<true>(m, h * DH + dim, H * DH)) = pk;
+                } else {
+                    f32x4_t v4 = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+                    *reinterpret_cast<f32x4_t *>(reinterpret_cast<float *>(out) + ((size_t)m * H + h) * DH + dim) = v4;
                 }
-            } else {
-                f32x4_t v4 = {acc[4 * g4], acc[4 * g4 + 1], acc[4 * g4 + 2], acc[4 * g4 + 3]};
-                *reinterpret_cast<f32x4_t *>(rec + (size_t)query * DH + dim) = v4;
             }
+        } else {
+            f32x4_t v4 = {acc[0], acc[1], acc[2], acc[3]};
+            *reinterpret_cast<f32x4_t *>(rec + (size_t)query * DH + dim) = v4;
         }
     }
     if (!final_out && kwv == 0 && hl == 0) {
