@@ -25,6 +25,8 @@
 //   longer contexts: QW waves of a workgroup take different query tiles, 8/QW
 //     waves split the keys, and several workgroups per (b, h) split the keys
 //     further; each leaves a (max, sum, O) record that attn_merge_kernel combines.
+#include <algorithm>
+
 #include "device_common.h"
 #include "internal.h"
 
@@ -358,12 +360,17 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
     const int tiles = ceil_div(len + T, 32);
     // Short contexts: one workgroup per 32-query tile, its 8 waves split the keys (up to five 32-key tiles each) and
     // the result goes straight out.  Longer ones: a CU streams at most ~45 GB/s, so the keys of one head are spread
-    // over several workgroups (about two tiles per wave) whose partial records attn_merge_kernel combines.
+    // over several workgroups (two tiles per wave or more) whose partial records attn_merge_kernel combines.
     int wgs = 1, qsplit = 0;
     if (tiles <= ATTN_WAVES * 5) {
         qsplit = 1; QW = 1; KWV = ATTN_WAVES; wgs = QTtot;
     } else {
+        // ... but never more workgroups than one round of the chip: a workgroup holds a CU by itself (registers), so
+        // a second round only repeats the fixed cost of a workgroup (first round trips, LDS merge, partial record).
+        // Measured best at about 200 workgroups in all: 7B at 2066 / 4114 keys 4.30 -> 4.01 / 4.63 -> 4.30 ms per verify.
         wgs = ceil_div(tiles, KWV * 2);
+        const int cap = std::max(1, 208 / (H * B));
+        if (wgs > cap) wgs = cap;
         if (wgs > units_max) wgs = units_max;
         if (wgs < 1) wgs = 1;
     }
