@@ -409,6 +409,9 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     const int mgroups = ceil_div(mblocks, p.mb);
     const int bands = ceil_div(N, 32), KT = K / 16;
     const bool pairs = kind == GEMM_KIND_PAIRS;                        // band pairs: exactly two bands per wave
+    // a partial output is M x N floats written and read back: the charge per split was fitted at 64 rows and grows
+    // with the rows beyond that (measured at 128 and 256 rows: verify 6.08 -> 5.74 and 10.05 -> 9.3 ms with 4x / 8x)
+    const double split_charge = split_us * (M > 64 ? M / 32.0 : 1.0);
     const bool may_split = kind == GEMM_KIND_PLAIN;
     p.nw = 1;
     // bands per wave: accumulators MB*NT*16 plus two prefetch sets must fit the register file
@@ -426,7 +429,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
             double cost = rounds * (w_bytes + x_bytes) / (cap_gbps * 1e3);   // us at the per-CU limit
             const double hbm = (double)N * K * 2 / (hbm_tbps * 1e6);         // us at the HBM limit
             if (cost < hbm) cost = hbm;
-            cost += (s > 1 ? 1.0 + split_us * s : 0.0);                      // reading S partials back costs a little
+            cost += (s > 1 ? 1.0 + split_charge * s : 0.0);                  // writing and reading S partials back
             if (cost < best_cost - 1e-9) { best_cost = cost; best_nt = nt; best_s = s; }
         }
     }
