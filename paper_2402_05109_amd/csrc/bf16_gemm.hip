@@ -415,7 +415,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     const bool may_split = kind == GEMM_KIND_PLAIN;
     p.nw = 1;
     // bands per wave: accumulators MB*NT*16 plus two prefetch sets must fit the register file
-    int nt_max = pairs ? 2 : (p.mb == 4 ? 3 : 4);
+    int nt_max = pairs ? (p.mb == 4 ? 2 : 4) : (p.mb == 4 ? 3 : 4);   // pairs: one or two band pairs per wave
     int best_nt = pairs ? 2 : 1, best_s = 1;
     double best_cost = 1e30;
     for (int nt = pairs ? 2 : 1; nt <= nt_max; nt += pairs ? 2 : 1) {
@@ -432,6 +432,10 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
             cost += (s > 1 ? 1.0 + split_charge * s : 0.0);                  // writing and reading S partials back
             if (cost < best_cost - 1e-9) { best_cost = cost; best_nt = nt; best_s = s; }
         }
+    }
+    if (pairs && p.mb <= 2) {                                          // tests: force one or two band pairs per wave
+        const int forced = (int)env_or("HYDRA_PLAN_PAIRS_NT", 0.0);
+        if (forced == 2 || forced == 4) best_nt = forced;
     }
     p.nt = best_nt;
     p.splits = best_s;
@@ -502,7 +506,9 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
     } else if constexpr (NT_SET == NT_TWO) {
         switch (key) {
             case 12: launch_one<1, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 14: launch_one<1, 4>(grid, block, lds, s, g, epi, e0, e1); break;
             case 22: launch_one<2, 2>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 24: launch_one<2, 4>(grid, block, lds, s, g, epi, e0, e1); break;
             case 42: launch_one<4, 2>(grid, block, lds, s, g, epi, e0, e1); break;
             default: return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
         }
@@ -657,6 +663,8 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
     if (e == hipSuccess) e = set_attr<1, 2, EpiQkvRope>();
     if (e == hipSuccess) e = set_attr<2, 2, EpiQkvRope>();
     if (e == hipSuccess) e = set_attr<4, 2, EpiQkvRope>();
+    if (e == hipSuccess) e = set_attr<1, 4, EpiQkvRope>();
+    if (e == hipSuccess) e = set_attr<2, 4, EpiQkvRope>();
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(gemm_bf16_kernel)");
     return HYDRA_OK;
 }

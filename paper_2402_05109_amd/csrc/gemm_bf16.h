@@ -30,9 +30,10 @@
 //       three may contain a workgroup barrier; what they leave in LDS is visible to tile() because a
 //       barrier separates streaming from the epilogue;
 //   begin(t, g): once per wave after that barrier, before its first tile.
-// An epilogue with PAIRED = true (NT = 2) instead receives both tiles of a band pair, four accumulator
-// registers (rows) at a time:  pair4(x0, x1, a, v0, t, g) with x0[q], x1[q] the registers v0 + q of the
-// tiles (a, 0) and (a, 1).  The 4*MB such items of a band group are shared out over the KW waves.
+// An epilogue with PAIRED = true (NT = 2 or 4: one or two band pairs per wave) instead receives both tiles of a
+// band pair, four accumulator registers (rows) at a time:  pair4(x0, x1, a, v0, t, g) with x0[q], x1[q] the
+// registers v0 + q of the pair's tiles in row block a, and t.tile0 the pair's first band.  The 4*MB items of
+// each pair are shared out over the KW waves.
 #pragma once
 
 #include <type_traits>
@@ -183,13 +184,18 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
         if (!live) return;
         epi.begin(t, g);
         if constexpr (Epilogue::PAIRED) {
-            static_for<MB>([&](auto A) {
-                static_for<4>([&](auto Q4) {
-                    constexpr int a = decltype(A)::value, q4 = decltype(Q4)::value;
-                    float x0[4], x1[4];
+            static_for<NT / 2>([&](auto PR) {
+                constexpr int pr = decltype(PR)::value;
+                GemmTile<MB, NT> tp = t;
+                tp.tile0 = t.tile0 + 2 * pr;
+                static_for<MB>([&](auto A) {
+                    static_for<4>([&](auto Q4) {
+                        constexpr int a = decltype(A)::value, q4 = decltype(Q4)::value;
+                        float x0[4], x1[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) { x0[q] = acc[a][0][4 * q4 + q]; x1[q] = acc[a][NT - 1][4 * q4 + q]; }
-                    epi.pair4(x0, x1, a, 4 * q4, t, g);
+                        for (int q = 0; q < 4; ++q) { x0[q] = acc[a][2 * pr][4 * q4 + q]; x1[q] = acc[a][2 * pr + 1][4 * q4 + q]; }
+                        epi.pair4(x0, x1, a, 4 * q4, tp, g);
+                    });
                 });
             });
         } else {
@@ -214,15 +220,18 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
     if (!live) return;
     epi.begin(t, g);
     if constexpr (Epilogue::PAIRED) {
-        for (int id = kw; id < MB * 4; id += g.KW) {               // wave-uniform
-            const int a = id >> 2, v0 = (id & 3) * 4;
+        for (int id = kw; id < MB * 4 * (NT / 2); id += g.KW) {    // wave-uniform
+            const int pr = id / (MB * 4), r = id - pr * (MB * 4);
+            const int a = r >> 2, v0 = (r & 3) * 4;
             float x0[4] = {0.f, 0.f, 0.f, 0.f}, x1[4] = {0.f, 0.f, 0.f, 0.f};
             for (int w = 0; w < g.KW; ++w) {
-                const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + a * NT) * 16 * 64 + lane;
+                const float *src = redbuf + ((size_t)(w * g.NW + nw) * TILES + a * NT + 2 * pr) * 16 * 64 + lane;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) { x0[q] += src[(v0 + q) * 64]; x1[q] += src[(16 * (NT - 1) + v0 + q) * 64]; }
+                for (int q = 0; q < 4; ++q) { x0[q] += src[(v0 + q) * 64]; x1[q] += src[(16 + v0 + q) * 64]; }
             }
-            epi.pair4(x0, x1, a, v0, t, g);
+            GemmTile<MB, NT> tp = t;
+            tp.tile0 = t.tile0 + 2 * pr;
+            epi.pair4(x0, x1, a, v0, tp, g);
         }
     } else {
 #pragma unroll

@@ -200,6 +200,14 @@ def test_tree_verify_forward_many_rows_kernel_on_a_small_model(min_wgs, monkeypa
     _verify_forward_teacher_forced("prior64", 16, 21)
 
 
+@pytest.mark.parametrize("tree_name,B,L", [("prior64", 1, 21), ("tiny16", 3, 17), ("single", 2, 9), ("prior32", 1, 40)])
+def test_tree_verify_forward_two_band_pairs_per_wave(tree_name, B, L, monkeypatch):
+    """The q|k|v GEMM with two band pairs per wave (the planner takes that shape when one pair per wave would need a
+    second, mostly empty round of workgroups, as at the 33B width); forced here on the small model, 1 and 2 row blocks."""
+    monkeypatch.setenv("HYDRA_PLAN_PAIRS_NT", "4")
+    _verify_forward_teacher_forced(tree_name, B, L)
+
+
 def test_tree_verify_forward_is_bitwise_the_same_without_the_kv_pre_read(monkeypatch):
     """The spare workgroups of the q|k|v launch only read cached K/V pages ahead of attention; switching them off
     must not change a single bit of any output (rows of different lengths, one of them empty)."""
