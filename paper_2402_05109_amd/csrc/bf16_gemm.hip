@@ -3,6 +3,8 @@
 // into its tile order.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include <algorithm>
 
 #include <hip/hip_ext.h>
@@ -416,6 +418,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     p.nw = 1;
     // bands per wave: accumulators MB*NT*16 plus two prefetch sets must fit the register file
     int nt_max = pairs ? (p.mb == 4 ? 2 : 4) : (p.mb == 4 ? 3 : 4);   // pairs: one or two band pairs per wave
+    if (kind == GEMM_KIND_SWIGLU && p.mb == 2) nt_max = 5;             // the widest instantiation (very wide FFNs: one round instead of two)
     int best_nt = pairs ? 2 : 1, best_s = 1;
     double best_cost = 1e30;
     for (int nt = pairs ? 2 : 1; nt <= nt_max; nt += pairs ? 2 : 1) {
@@ -433,6 +436,7 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
             if (cost < best_cost - 1e-9) { best_cost = cost; best_nt = nt; best_s = s; }
         }
     }
+    if (kind == GEMM_KIND_SWIGLU && p.mb == 2 && env_or("HYDRA_PLAN_SWIGLU_NT", 0.0) == 5.0) best_nt = 5, best_s = 1;   // tests: force the widest shape
     if (pairs && p.mb <= 2) {                                          // tests: force one or two band pairs per wave
         const int forced = (int)env_or("HYDRA_PLAN_PAIRS_NT", 0.0);
         if (forced == 2 || forced == 4) best_nt = forced;
@@ -522,6 +526,9 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
             case 22: launch_one<2, 2>(grid, block, lds, s, g, epi, e0, e1); break;
             case 23: launch_one<2, 3>(grid, block, lds, s, g, epi, e0, e1); break;
             case 24: launch_one<2, 4>(grid, block, lds, s, g, epi, e0, e1); break;
+            case 25:
+                if constexpr (std::is_same<Epi, EpiSilu>::value) { launch_one<2, 5>(grid, block, lds, s, g, epi, e0, e1); break; }
+                else return fail(HYDRA_E_UNSUPPORTED, "gemm: no kernel for this plan");
             case 41: launch_one<4, 1>(grid, block, lds, s, g, epi, e0, e1); break;
             case 42: launch_one<4, 2>(grid, block, lds, s, g, epi, e0, e1); break;
             case 43: launch_one<4, 3>(grid, block, lds, s, g, epi, e0, e1); break;
@@ -608,7 +615,7 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
 
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act) {
-    GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_FUSED);
+    GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_SWIGLU);
     EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (a16_t *)act, F};
     return launch_bf16<EpiSilu, NT_ANY>(c, s, X, W, M, 2 * F, K, p, epi);
 }
@@ -663,6 +670,7 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
     if (e == hipSuccess) e = set_attr<1, 2, EpiQkvRope>();
     if (e == hipSuccess) e = set_attr<2, 2, EpiQkvRope>();
     if (e == hipSuccess) e = set_attr<4, 2, EpiQkvRope>();
+    if (e == hipSuccess) e = set_attr<2, 5, EpiSilu>();
     if (e == hipSuccess) e = set_attr<1, 4, EpiQkvRope>();
     if (e == hipSuccess) e = set_attr<2, 4, EpiQkvRope>();
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(gemm_bf16_kernel)");

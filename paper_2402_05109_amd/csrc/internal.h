@@ -100,7 +100,7 @@ struct WsLayout {
     int attn_units;     // split-KV units per (row, head, query group)
 };
 WsLayout ws_layout(const hydra_ctx *c, int B);
-enum { GEMM_KIND_PLAIN = 0, GEMM_KIND_FUSED = 1, GEMM_KIND_PAIRS = 2 };   // plain output (may split K) / fused epilogue / gate-up pairs
+enum { GEMM_KIND_PLAIN = 0, GEMM_KIND_FUSED = 1, GEMM_KIND_PAIRS = 2, GEMM_KIND_SWIGLU = 3 };   // plain output (may split K) / fused epilogue / q|k|v band pairs / gate-up (fused, up to five bands per wave)
 GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind);
 int      attn_units(const hydra_ctx *c, int B);
 

@@ -208,6 +208,14 @@ def test_tree_verify_forward_two_band_pairs_per_wave(tree_name, B, L, monkeypatc
     _verify_forward_teacher_forced(tree_name, B, L)
 
 
+@pytest.mark.parametrize("tree_name,B,L", [("prior64", 1, 21), ("tiny16", 3, 17), ("prior32", 2, 40)])
+def test_tree_verify_forward_five_bands_per_wave_in_gate_up(tree_name, B, L, monkeypatch):
+    """The gate/up GEMM with five bands per wave (the planner takes that shape for very wide FFNs, where four would
+    need a second round of workgroups); forced here on the small model, whose 24 bands leave the last wave a ragged four."""
+    monkeypatch.setenv("HYDRA_PLAN_SWIGLU_NT", "5")
+    _verify_forward_teacher_forced(tree_name, B, L)
+
+
 def test_tree_verify_forward_is_bitwise_the_same_without_the_kv_pre_read(monkeypatch):
     """The spare workgroups of the q|k|v launch only read cached K/V pages ahead of attention; switching them off
     must not change a single bit of any output (rows of different lengths, one of them empty)."""
