@@ -1,6 +1,7 @@
 // bf16 storage family: launch plans and epilogues of the weight-streaming GEMM
 // (kernel in gemm_bf16.h), and the kernels that bring plain row-major weights
 // into its tile order.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <type_traits>
@@ -453,18 +454,33 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     // faster at 8): the X tiles both groups read count against the CU's request path even when they hit in L1.
     if (mgroups >= 6 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }
     p.kpw = ceil_div(KT, p.kw * p.splits);
-    // Four or more row groups of 128 rows: the X tiles dominate, and enough workgroups remain when 4 or 8 waves take
-    // different band pairs and share X through LDS (gemm_bf16_sharedx_kernel).  No K split in that shape.
-    if (p.mb == 4 && mgroups >= 4 && KT >= 16) {
+    // Two or more row groups of 128 rows: the X tiles dominate, and where enough workgroups remain 4 or 8 waves take
+    // different band pairs and share X through LDS (gemm_bf16_sharedx_kernel; no K split in that shape).  A workgroup
+    // then pulls NWT pairs of W and X once; the shape is taken where that costs less than the plan above.
+    if (p.mb == 4 && mgroups >= 2 && KT >= 16) {
         const int groups2 = ceil_div(bands, 2);
-        const int min_wgs = (int)env_or("HYDRA_PLAN_SHARED_X_MIN_WGS", 160.0);    // tests lower it to reach this shape with small models
-        for (int nwt = 8; nwt >= 4; nwt >>= 1) {
-            if (ceil_div(groups2, nwt) * mgroups >= min_wgs) {
-                p.shared_x = nwt; p.nt = 2; p.nw = nwt; p.kw = 1; p.splits = 1; p.kpw = KT;
-                break;
+        int pick = 0;
+        if (getenv("HYDRA_PLAN_SHARED_X_MIN_WGS")) {                  // tests: the shape wherever this many workgroups remain
+            const int min_wgs = (int)env_or("HYDRA_PLAN_SHARED_X_MIN_WGS", 160.0);
+            for (int nwt = 8; nwt >= 4 && !pick && mgroups >= 4; nwt >>= 1)
+                if (ceil_div(groups2, nwt) * mgroups >= min_wgs) pick = nwt;
+        } else {
+            double best = p.cost_us;
+            const double hbm = (double)N * K * 2 / (hbm_tbps * 1e6);
+            for (int nwt = 8; nwt >= 4; nwt >>= 1) {
+                const int wgs = ceil_div(groups2, nwt) * mgroups;
+                const double bytes = (double)nwt * 64 * K * 2 + 128.0 * K * 2;
+                double cost = ceil_div(wgs, 256) * bytes / (cap_gbps * 1e3);
+                if (cost < hbm) cost = hbm;
+                if (wgs >= 128 && cost < 0.97 * best) { best = cost; pick = nwt; }      // a tie goes to the plan with more workgroups
             }
+            if (pick) p.cost_us = (float)best;
         }
+        if (pick) { p.shared_x = pick; p.nt = 2; p.nw = pick; p.kw = 1; p.splits = 1; p.kpw = KT; }
     }
+    if (getenv("HYDRA_PLAN_DEBUG"))
+        fprintf(stderr, "plan M=%d N=%d K=%d kind=%d -> mb=%d nt=%d nw=%d kw=%d splits=%d shared_x=%d cost=%.1f\n", M, N, K, kind, p.mb, p.nt, p.nw,
+                p.kw, p.splits, p.shared_x, p.cost_us);
     return p;
 }
 
