@@ -478,7 +478,8 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
         }
         if (pick) { p.shared_x = pick; p.nt = 2; p.nw = pick; p.kw = 1; p.splits = 1; p.kpw = KT; }
     }
-    if (getenv("HYDRA_PLAN_DEBUG"))
+    static const bool debug = getenv("HYDRA_PLAN_DEBUG") != nullptr;       // tuning aid: every plan to stderr
+    if (debug)
         fprintf(stderr, "plan M=%d N=%d K=%d kind=%d -> mb=%d nt=%d nw=%d kw=%d splits=%d shared_x=%d cost=%.1f\n", M, N, K, kind, p.mb, p.nt, p.nw,
                 p.kw, p.splits, p.shared_x, p.cost_us);
     return p;
