@@ -38,24 +38,25 @@ def test_oracle_reproduces_stored_tokens():
 @pytest.mark.gpu
 def test_library_generation_equals_stored_tokens():
     import torch
-    from gpu_util import gpu_session, near_tie
+    from gpu_util import generate_checked, gpu_session
     cfg = CONFIGS[1]
     W = make_weights(cfg, gain_std=0.0)
     prompt = uniform_tokens(cfg.seed, 0, cfg.prompt[0], cfg.V)
-    sess = gpu_session(cfg, frozen_tree("tiny16"), 1, cfg.prompt[0] + cfg.gen + 8, W, prefill_chunk=32)
+    make = lambda: gpu_session(cfg, frozen_tree("tiny16"), 1, cfg.prompt[0] + cfg.gen + 8, W, prefill_chunk=32)
+    sess = make()
     sess.prefill(prompt.reshape(1, -1))
     sess.draft()
     torch.cuda.synchronize()
     first_tree = sess.out().tree_tokens[0].cpu().tolist()
-    toks, accs = sess.generate(cfg.gen)
-    assert sess.main.read_flags() == 0
     truth = GOLD["greedy_tokens"]
-    if toks[0] != truth:
-        m = oracle_model(cfg, W)
-        i = next(j for j in range(cfg.gen) if toks[0][j] != truth[j])
-        cache = O.FlatCache(m, len(prompt) + i + 1)
-        _, _, _, lg = O.ar_prefill(m, cache, prompt.tolist() + truth[:i])
-        assert near_tie(lg, 1e-4), f"token {i} differs from the stored greedy token and is not a near-tie"
-        pytest.skip("diverged at a counted near-tie")
+    segments, near_ties = generate_checked(make, prompt, truth, cfg.gen, oracle_model(cfg, W), 1e-4)
+    accs = segments[0][2]
+    if near_ties:                                         # acceptance lengths are comparable up to the first restart
+        emitted, keep = 0, 0
+        for a in accs:
+            if emitted + a[0] > len(segments[0][1]):
+                break
+            emitted += a[0]; keep += 1
+        accs = accs[:keep]
     assert [a[0] for a in accs] == GOLD["hydra_acceptance"][:len(accs)]
     assert first_tree == GOLD["first_draft_tree_tokens"]

@@ -14,7 +14,7 @@ import torch
 from oracle import hydra_oracle as O
 from synth import chain_tree, frozen_tree, random_tree, star_tree, uniform_tokens
 from helpers import make_weights, oracle_model, small_shape
-from gpu_util import gpu_session, load_oracle_cache, max_rel, near_tie, read_cache, to_np
+from gpu_util import VerifyAudit, gpu_session, load_oracle_cache, max_rel, near_tie, read_cache, to_np
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -268,25 +268,18 @@ def _verify_forward_teacher_forced(tree_name, B, L):
     torch.cuda.synchronize()
     assert sess.main.read_flags() == 0
     newkv = read_cache(sess, sess.main, L, T)
-    skipped = checked = 0
-    worst_h = worst_l = 0.0
+    audit = VerifyAudit(TOL)
+    worst_h = 0.0
     for b in range(B):
         hid, logits, amax = O.tree_verify(m, caches[b], L, tree, toks[b])
-        worst_h = max(worst_h, max_rel(to_np(o.hidden[b]), hid)); worst_l = max(worst_l, max_rel(to_np(o.logits[b]), logits))
-        for n in range(T):
-            g = int(o.argmax[b, n])
-            if near_tie(logits[n], TOL):
-                skipped += 1
-                assert logits[n][g] >= np.max(logits[n]) - TOL * np.max(np.abs(logits[n]))
-                continue
-            checked += 1
-            assert g == amax[n]
+        worst_h = max(worst_h, max_rel(to_np(o.hidden[b]), hid))
+        audit.add(o.logits[b].cpu().numpy(), o.argmax[b].cpu().numpy(), o.margin[b].cpu().numpy(), logits, amax)
         for l in range(cfg.NL):
             assert max_rel(newkv[l, b, :, 0].reshape(T, -1), caches[b].K[l, L:L + T].reshape(T, -1)) <= TOL
             assert max_rel(newkv[l, b, :, 1].reshape(T, -1), caches[b].V[l, L:L + T].reshape(T, -1)) <= TOL
-    print("hidden err", worst_h, "logits err", worst_l, "argmax checked", checked, "near-tie skipped", skipped, flush=True)
-    assert worst_h <= TOL and worst_l <= TOL
-    assert checked > 0
+    print("hidden err", worst_h, flush=True)
+    assert worst_h <= TOL
+    audit.finish(f"{tree_name} B={B} L={L}", max_skip_frac=0.3)
 
 
 def test_generation_free_running_until_first_near_tie():

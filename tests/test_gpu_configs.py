@@ -17,7 +17,7 @@ import torch
 from oracle import hydra_oracle as O
 from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor, tensor_names, uniform_tokens
 from helpers import oracle_model
-from gpu_util import load_oracle_cache, max_rel, near_tie, read_cache, to_np
+from gpu_util import VerifyAudit, load_oracle_cache, max_rel, read_cache, to_np
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -105,19 +105,13 @@ def test_draft_and_verify_at_full_width(idx, over, B, lens):
     torch.cuda.synchronize()
     assert sess.main.read_flags() == 0
     worst = dict(h=0.0, l=0.0, k=0.0, v=0.0)
-    skipped = 0
+    audit = VerifyAudit(TOL)
     for b in range(B):
         L = lens[b]
         hid, logits, amax = O.tree_verify(m, caches[b], L, tree, toks[b].tolist())
         worst["h"] = max(worst["h"], max_rel(to_np(o.hidden[b]), hid))
         worst["l"] = max(worst["l"], max_rel(to_np(o.logits[b]), logits))
-        for n in range(T):
-            g = int(o.argmax[b, n])
-            if near_tie(logits[n], TOL):
-                skipped += 1
-                assert logits[n][g] >= np.max(logits[n]) - TOL * np.max(np.abs(logits[n]))
-            else:
-                assert g == amax[n]
+        audit.add(o.logits[b].cpu().numpy(), o.argmax[b].cpu().numpy(), o.margin[b].cpu().numpy(), logits, amax)
         for l in range(cfg.NL):
             t = torch.zeros(B, T, 2, cfg.H, cfg.Dh, dtype=torch.float32, device=dev)
             sess.main.kv_read(B, l, sess.kv, L, T, t)
@@ -165,6 +159,6 @@ def test_draft_and_verify_at_full_width(idx, over, B, lens):
     assert worst_p <= TOL
 
     print(f"config {idx} {over} B={B}: draft {exact} nodes exact / {audited} audited; verify hidden {worst['h']:.4f} "
-          f"logits {worst['l']:.4f} K {worst['k']:.4f} V {worst['v']:.4f}; {skipped} near-tie rows of {B * T}", flush=True)
+          f"logits {worst['l']:.4f} K {worst['k']:.4f} V {worst['v']:.4f}", flush=True)
     assert max(worst.values()) <= TOL
-    assert B * T - skipped >= B * T // 2
+    audit.finish(f"config {idx} B={B}", max_skip_frac=0.2)

@@ -17,7 +17,7 @@ import torch
 from oracle import hydra_oracle as O
 from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor, tensor_names, uniform_tokens
 from helpers import oracle_model
-from gpu_util import load_oracle_cache, max_rel, near_tie, read_cache, to_np
+from gpu_util import VerifyAudit, load_oracle_cache, max_rel, read_cache, to_np
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -64,22 +64,16 @@ def test_tree_verify_forward_full_width(full):
     torch.cuda.synchronize()
     assert sess.main.read_flags() == 0
     hid, logits, amax = O.tree_verify(m, cache, L, tree, toks)
-    eh, el = max_rel(to_np(o.hidden[0]), hid), max_rel(to_np(o.logits[0]), logits)
-    skipped = 0
-    for n in range(T):
-        g = int(o.argmax[0, n])
-        if near_tie(logits[n], TOL):
-            skipped += 1
-            assert logits[n][g] >= np.max(logits[n]) - TOL * np.max(np.abs(logits[n]))
-        else:
-            assert g == amax[n]
+    eh = max_rel(to_np(o.hidden[0]), hid)
+    audit = VerifyAudit(TOL)
+    audit.add(o.logits[0].cpu().numpy(), o.argmax[0].cpu().numpy(), o.margin[0].cpu().numpy(), logits, amax)
+    el, skipped = audit.finish("full width, 2 layers", max_skip_frac=0.2)
     newkv = read_cache(sess, sess.main, L, T)
     ek = max(max_rel(newkv[l, 0, :, 0].reshape(T, -1), cache.K[l, L:L + T].reshape(T, -1)) for l in range(cfg.NL))
     ev = max(max_rel(newkv[l, 0, :, 1].reshape(T, -1), cache.V[l, L:L + T].reshape(T, -1)) for l in range(cfg.NL))
     print(f"full width: hidden err {eh:.4f} logits err {el:.4f} K err {ek:.4f} V err {ev:.4f}; "
           f"argmax exact on {T - skipped} rows, {skipped} near-tie rows", flush=True)
     assert eh <= TOL and el <= TOL and ek <= TOL and ev <= TOL
-    assert T - skipped >= T // 2
 
 
 def test_draft_tree_full_width(full):
@@ -172,14 +166,11 @@ def test_tree_verify_forward_full_depth_32_layers():
     assert sess.main.read_flags() == 0
     print("GPU verify done, oracle running", flush=True)
     hid, logits, amax = O.tree_verify(m, cache, L, tree, toks)
-    eh, el = max_rel(to_np(o.hidden[0]), hid), max_rel(to_np(o.logits[0]), logits)
-    skipped = 0
-    for n in range(T):
-        g = int(o.argmax[0, n])
-        if near_tie(logits[n], TOL):
-            skipped += 1
-            assert logits[n][g] >= np.max(logits[n]) - TOL * np.max(np.abs(logits[n]))
-        else:
-            assert g == amax[n]
+    eh = max_rel(to_np(o.hidden[0]), hid)
+    audit = VerifyAudit(TOL)
+    audit.add(o.logits[0].cpu().numpy(), o.argmax[0].cpu().numpy(), o.margin[0].cpu().numpy(), logits, amax)
+    # the near-tie threshold follows the error measured here, which after 32 layers is about four times that of the
+    # 2-layer cases: with random-init logits over 32000 ids roughly a third of the rows then lie under it
+    el, skipped = audit.finish("full width, 32 layers", max_skip_frac=0.5)
     print(f"32 layers: hidden err {eh:.4f} logits err {el:.4f}; argmax exact on {T - skipped} rows, {skipped} near-tie rows", flush=True)
     assert eh <= TOL and el <= TOL

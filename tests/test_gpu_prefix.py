@@ -11,7 +11,7 @@ import torch
 from oracle import hydra_oracle as O
 from synth import CONFIGS, WeightSpec, chain_tree, frozen_tree, make_tensor, tensor_names, uniform_tokens
 from helpers import make_weights, oracle_model, small_shape
-from gpu_util import gpu_session, max_rel, near_tie, to_np
+from gpu_util import generate_checked, gpu_session, max_rel, near_tie, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +62,7 @@ def test_prefill_and_scripted_steps_match_the_oracle(dtype, tol, Dh, d, H):
     want = [[4, 1, 2, 3], [1, 3, 4, 2]]
     L = [12] * B
     o = sess.out()
+    near_ties = 0
     for step in range(4):
         sess.draft()
         torch.cuda.synchronize()
@@ -96,9 +97,14 @@ def test_prefill_and_scripted_steps_match_the_oracle(dtype, tol, Dh, d, H):
             n_acc, path, nxt, last = O.accept_greedy(tree, toks[b].tolist(), amax)
             if dtype == "f32":
                 assert n_acc == want[b][step]
-            if int(o.n_acc[b]) != n_acc:                      # 16-bit family: only legitimate at an oracle near-tie
-                assert any(near_tie(logits[n], tol) for n in path)
-                pytest.skip("acceptance differs at a counted near-tie")
+            gp = o.path[b, :int(o.n_acc[b])].tolist()
+            if gp != path:
+                # 16-bit family: the two walks may part only at a node whose oracle top-2 margin is a near-tie; it
+                # is counted and the oracle goes on along the library's path, so every later step is still compared
+                k = next((j for j in range(min(len(gp), len(path))) if gp[j] != path[j]), min(len(gp), len(path)))
+                assert k >= 1 and near_tie(logits[gp[k - 1]], tol), f"step {step} row {b}: acceptance differs away from a near-tie"
+                near_ties += 1
+                path, n_acc = gp, len(gp)
             O.kv_compact(caches[b], L[b], path)
             for j, n in enumerate(path):
                 g = O.prefix_token(m, pcs[b], hid[n], L[b] + j)
@@ -108,6 +114,8 @@ def test_prefill_and_scripted_steps_match_the_oracle(dtype, tol, Dh, d, H):
             assert max_rel(got[b, :, 1].reshape(n_acc, -1), pcs[b].V[L[b]:L[b] + n_acc].reshape(n_acc, -1)) <= tol
             L[b] += n_acc
         assert sess.pseq_len.tolist() == L and sess.seq_len.tolist() == L
+    print("acceptance decisions at a near-tie:", near_ties, flush=True)
+    assert near_ties <= 1
 
 
 def test_generation_with_prefix_layer_equals_oracle():
@@ -121,16 +129,11 @@ def test_generation_with_prefix_layer_equals_oracle():
     truth = O.ar_generate(m, prompt.tolist(), 32)
     want_tokens, want_acc = O.hydra_generate(m, tree, prompt.tolist(), 32, prefix=True)
     assert want_tokens == truth
-    sess = gpu_session(cfg, frozen_tree("tiny16"), 1, 64 + 32 + 8, W, prefill_chunk=32)
-    sess.prefill(prompt.reshape(1, -1))
-    toks, accs = sess.generate(32)
-    assert sess.main.read_flags() == 0
-    if toks[0] != truth:
-        i = next(j for j in range(32) if toks[0][j] != truth[j])
-        cache = O.FlatCache(m, len(prompt) + i + 1)
-        _, _, _, lg = O.ar_prefill(m, cache, prompt.tolist() + truth[:i])
-        assert near_tie(lg, 1e-4), f"token {i} differs and is not a near-tie"
-        pytest.skip("diverged at a counted near-tie")
+    make = lambda: gpu_session(cfg, frozen_tree("tiny16"), 1, 64 + 32 + 8, W, prefill_chunk=32)
+    segments, near_ties = generate_checked(make, prompt, truth, 32, m, 1e-4)
+    accs = segments[0][2]
+    if near_ties:
+        return                                            # all 32 tokens were compared; acceptance lengths only without a restart
     assert [a[0] for a in accs] == want_acc[:len(accs)]
 
 

@@ -12,7 +12,7 @@ from oracle import hydra_oracle as O
 from synth import uniform_tokens
 from synth.trees import build_prior_tree
 from helpers import make_weights, oracle_model, small_shape
-from gpu_util import gpu_session, load_oracle_cache, max_rel, near_tie, read_cache, to_np
+from gpu_util import VerifyAudit, gpu_session, load_oracle_cache, max_rel, read_cache, to_np
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
@@ -91,21 +91,17 @@ def test_random_shape_draft_and_verify(seed):
     sess.verify()
     torch.cuda.synchronize()
     assert sess.main.read_flags() == 0
-    checked = 0
+    audit = VerifyAudit(TOL)
     for b in range(B):
         L = lens[b]
         hid, logits, amax = O.tree_verify(m, caches[b], L, tree, toks[b].tolist())
         assert max_rel(to_np(o.hidden[b]), hid) <= TOL and max_rel(to_np(o.logits[b]), logits) <= TOL
-        for n in range(T):
-            g = int(o.argmax[b, n])
-            if near_tie(logits[n], TOL):
-                assert logits[n][g] >= np.max(logits[n]) - TOL * np.max(np.abs(logits[n]))
-            else:
-                assert g == amax[n]; checked += 1
+        audit.add(o.logits[b].cpu().numpy(), o.argmax[b].cpu().numpy(), o.margin[b].cpu().numpy(), logits, amax)
         for l in range(cfg.NL):
             t = torch.zeros(B, T, 2, cfg.H, cfg.Dh, dtype=torch.float32, device="cuda:0")
             sess.main.kv_read(B, l, sess.kv, L, T, t)
             kv = to_np(t[b])
             assert max_rel(kv[:, 0].reshape(T, -1), caches[b].K[l, L:L + T].reshape(T, -1)) <= TOL
             assert max_rel(kv[:, 1].reshape(T, -1), caches[b].V[l, L:L + T].reshape(T, -1)) <= TOL
-    print(f"seed {seed}: draft {exact} exact / {audited} audited, verify argmax checked on {checked} rows", flush=True)
+    print(f"seed {seed}: draft {exact} exact / {audited} audited", flush=True)
+    audit.finish(f"seed {seed}", max_skip_frac=0.3)

@@ -42,6 +42,27 @@ def test_residual_form_closed_forms():
     np.testing.assert_allclose(O.head_logits(m, 1, h, [3]), Wout @ (h + s), rtol=0, atol=1e-12)
 
 
+def test_first_layer_orientation_with_a_non_symmetric_matrix():
+    """z = h + SiLU(W1 h + b1) with W1 [out, in] (section 2, "Medusa decoding": one hidden layer with a skip
+    connection).  W1 holds W1[r, c] = 1.5 and W1[c, q] = -2 only, so W1 h is written out by hand:
+    (W1 h)[r] = 1.5 h[c], (W1 h)[c] = -2 h[q]; the transposed product differs and is told apart."""
+    cfg = small_shape(medusa=1, K=1)
+    W = dict(make_weights(cfg, std=0.3))
+    d = cfg.d
+    r, c, q = 2, 11, 7
+    W1 = torch.zeros(d, d); W1[r, c] = 1.5; W1[c, q] = -2.0
+    W["heads.1.w1"] = W1
+    h = np.random.default_rng(3).standard_normal(d)
+    pre = W["heads.1.b1"].double().numpy().copy()
+    pre[r] += 1.5 * h[c]
+    pre[c] += -2.0 * h[q]
+    z = h + pre / (1.0 + np.exp(-pre))
+    want = W["heads.1.wout"].double().numpy() @ z
+    np.testing.assert_allclose(O.head_logits(oracle_model(cfg, W), 1, h, [3]), want, rtol=0, atol=1e-12)
+    Wt = dict(W); Wt["heads.1.w1"] = W1.t().contiguous()
+    assert np.max(np.abs(O.head_logits(oracle_model(cfg, Wt), 1, h, [3]) - want)) > 1e-3
+
+
 def test_greedy_output_unchanged_with_medusa_heads():
     cfg = small_shape(medusa=1)
     W = make_weights(cfg, gain_std=0.2, std=0.3)

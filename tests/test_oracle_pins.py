@@ -328,6 +328,36 @@ def test_hydrapp_residual_layers_closed_form():
                                W["heads.1.wout"].double().numpy() @ z, atol=1e-13)
 
 
+def test_hydrapp_residual_layer_orientation_with_a_non_symmetric_matrix():
+    """Section 3.1 "Scaling": layer j >= 2 is z + SiLU(W_j z + b_j) with W_j [out, in].  W_j holds two entries only,
+    W_j[r, c] = 2 and W_j[c, q] = -1 (r, c, q distinct), so that W_j z is written out by hand element by element:
+    (W z)[r] = 2 z[c], (W z)[c] = -z[q], zero elsewhere.  The transposed product would put 2 z[r] into element c and
+    -z[c] into element q instead, which this comparison tells apart."""
+    cfg = small_shape(mlp_layers=3, K=1)
+    W = dict(make_weights(cfg, std=0.3))
+    d = cfg.d
+    h = np.random.default_rng(12).standard_normal(d)
+    E = W["embed"].double().numpy()
+    sil = lambda v: v / (1.0 + np.exp(-v))
+    z = sil(W["heads.1.w1"].double().numpy() @ np.concatenate([h, E[4]]) + W["heads.1.b1"].double().numpy())   # layer 1: pinned by the selector tests
+    for j, (r, c, q) in ((2, (3, 17, 5)), (3, (20, 1, 9))):
+        Wj = torch.zeros(d, d); Wj[r, c] = 2.0; Wj[c, q] = -1.0
+        W[f"heads.1.w{j}"] = Wj
+        b = W[f"heads.1.b{j}"].double().numpy()
+        pre = b.copy()
+        pre[r] += 2.0 * z[c]
+        pre[c] += -1.0 * z[q]
+        z = z + sil(pre)
+    want = W["heads.1.wout"].double().numpy() @ z
+    got = O.head_logits(oracle_model(cfg, W), 1, h, [4])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    # and the comparison does tell the transpose apart
+    Wt = dict(W)
+    for j in (2, 3):
+        Wt[f"heads.1.w{j}"] = W[f"heads.1.w{j}"].t().contiguous()
+    assert np.max(np.abs(O.head_logits(oracle_model(cfg, Wt), 1, h, [4]) - want)) > 1e-3
+
+
 def test_P1_top_k_equals_full_stable_sort_with_planted_ties():
     rng = np.random.default_rng(5)
     for trial in range(50):
