@@ -180,8 +180,10 @@ size_t hydra_workspace_bytes(const hydra_ctx *ctx, int B);
  * this function (or since hydra_bind_weights): bit 0 = a row's seq_len + T
  * exceeded its page table or max_pos (row skipped), bit 1 = a token id outside
  * [0, V) (treated as 0), bit 2 = hydra_prefix_attention met an n_acc outside
- * [1, P] or a path entry outside [0, T_src) (clamped).  Reads and clears them;
- * synchronises the stream. */
+ * [1, P] or a path entry outside [0, T_src) (clamped), bit 3 = a bounded wait
+ * inside the persistent layer kernel expired (see hydra_layer_kernel_info; the
+ * outputs of that call are undefined).  Reads and clears them; synchronises the
+ * stream. */
 int hydra_read_flags(hydra_ctx *ctx, void *stream, int32_t *flags_out /* host */);
 
 /* ---- the hot path -------------------------------------------------------- */
@@ -293,6 +295,19 @@ int hydra_kv_write(hydra_ctx *ctx, void *stream, int B, int layer, const hydra_k
                    int first_slot, int n_slots, const float *kv_plain);
 int hydra_kv_read(hydra_ctx *ctx, void *stream, int B, int layer, const hydra_kv *kv,
                   int first_slot, int n_slots, float *kv_plain);
+
+/* The persistent layer kernel (bf16 family): a tree_verify_forward of at most 64 rows whose kv->seq_len_hint is
+ * positive and at most 1280 - T can run all its decoder layers as one kernel with one workgroup per compute unit
+ * (section 2, "Tree decoding": the verification forward; the split into kernels is this library's).  Its grid-wide
+ * hand-offs wait with a bound: if not all workgroups become resident (another kernel holds compute units for
+ * seconds) the call ends with flag bit 3 set (hydra_read_flags) and undefined outputs, never with a hang.
+ *   info[0] = 1 if B rows can take that kernel, info[1] = byte offset inside the workspace of its timeline stamps
+ *   ([n_layers][info[3]][info[2]][8] int64 ticks of the 100 MHz wall clock: step begins, work done, arrived, released,
+ *   then inside GEMM steps first activations loaded, last MFMA issued, epilogue stores issued;
+ *   written only while the environment variable HYDRA_LAYER_KERNEL_STAMPS is 1), info[2] = workgroups, info[3] =
+ *   steps per layer.  The kernel is used only while the environment variable
+ *   HYDRA_LAYER_KERNEL is 1 (measured, it does not yet beat the multi-kernel path at the 7B shape). */
+int hydra_layer_kernel_info(const hydra_ctx *ctx, int B, int64_t *info /* host [4] */);
 
 /* Per-kernel-family timing with HIP events on `stream` (for benchmarks).
  * hydra_profile_begin switches it on and zeroes the counters; every launch of

@@ -25,7 +25,7 @@ E_INVALID_ARG, E_SHAPE, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_STATE = -1, -2, -3, 
 EXPORTS = ["hydra_create", "hydra_destroy", "hydra_last_error", "hydra_weights_bytes", "hydra_bind_weights",
            "hydra_load_tensor", "hydra_workspace_bytes", "hydra_read_flags", "hydra_draft_tree",
            "tree_verify_forward", "tree_attention", "accept_greedy", "accept_typical", "kv_compact", "hydra_prefix_attention", "hydra_tree_depth",
-           "hydra_kv_write", "hydra_kv_read", "hydra_profile_begin", "hydra_profile_end"]
+           "hydra_kv_write", "hydra_kv_read", "hydra_profile_begin", "hydra_profile_end", "hydra_layer_kernel_info"]
 
 
 class ModelDesc(C.Structure):
@@ -79,6 +79,7 @@ def _load() -> C.CDLL:
     lib.hydra_kv_write.argtypes = [vp, vp, i32, i32, C.POINTER(KVDesc), i32, i32, vp]
     lib.hydra_kv_read.argtypes = [vp, vp, i32, i32, C.POINTER(KVDesc), i32, i32, vp]
     lib.hydra_profile_begin.argtypes = [vp]
+    lib.hydra_layer_kernel_info.argtypes = [vp, i32, C.POINTER(C.c_int64)]
     lib.hydra_profile_end.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     return lib
 
@@ -229,6 +230,11 @@ class Hydra:
         d = kv.desc()
         _check(_lib.hydra_kv_read(self._h, _stream(), B, layer, C.byref(d), first_slot, n_slots,
                                   _ptr(plain, torch.float32, "kv_plain")))
+
+    def layer_kernel_info(self, B: int):
+        info = (C.c_int64 * 4)()
+        _check(_lib.hydra_layer_kernel_info(self._h, B, info))
+        return list(info)
 
     def profile_begin(self) -> None:
         _check(_lib.hydra_profile_begin(self._h))

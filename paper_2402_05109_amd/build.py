@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libhydra.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["api.hip", "glue.hip", "draft_accept.hip", "f32_family.hip", "bf16_gemm.hip", "bf16_attn.hip"]
+SOURCES = ["api.hip", "glue.hip", "draft_accept.hip", "f32_family.hip", "bf16_gemm.hip", "bf16_attn.hip", "bf16_layers.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -45,7 +45,7 @@ def build_library(verbose: bool = True) -> str:
         if verbose:
             print("compiled", SOURCES[i], flush=True)
 
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
         list(ex.map(one, range(len(SOURCES))))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs])
     if verbose:

@@ -142,6 +142,7 @@ WsLayout ws_layout(const hydra_ctx *c, int B) {
     w.z = off;     off += align_up(std::max<size_t>(Md, 1) * d * 4, 256);
     w.ss = off;    off += align_up((d / 32 + 1) * rows * 4, 256);
     w.topk = off;  off += align_up(topk_scratch_bytes(c, (int)std::max<size_t>(Md, 1)), 256);
+    w.mega = off;  off += align_up(layers_mega_ws_bytes(c, B), 256);     // per-layer buffers of the persistent layer kernel (0 if the shape cannot take it)
     w.total = off;
     return w;
 }
@@ -206,6 +207,12 @@ int hydra_create(const hydra_model_desc *m, const hydra_heads_desc *h, const hyd
     c->bf16 = m->dtype == HYDRA_BF16;
     c->esz = c->bf16 ? 2 : 4;
     c->arena = nullptr; c->table_slot = 0;
+    {   // compute units of the current device; without a device (host-only checks) the MI355X figure
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        (void)hipGetLastError();
+        c->n_cus = cus;
+    }
     c->profiling = false; c->ev_used = 0; c->prof_bytes = 0; c->prof_launches = 0;
     std::string why;
     int rc = build_tree(t, &c->tree, &why);
@@ -258,6 +265,7 @@ int hydra_bind_weights(hydra_ctx *c, void *stream, void *arena, int table_slot) 
         int rc = gemm_max_dynamic_lds(c);
         if (rc) return rc;
         if ((rc = attn_max_dynamic_lds(c))) return rc;
+        if ((rc = layers_mega_set_attr(c))) return rc;
     }
     return HYDRA_OK;
 }
@@ -310,6 +318,19 @@ int hydra_read_flags(hydra_ctx *c, void *stream, int32_t *flags_out) {
     HYDRA_HIP(hipMemcpyAsync(flags_out, flags_ptr(c), 4, hipMemcpyDeviceToHost, s));
     HYDRA_HIP(hipMemsetAsync(flags_ptr(c), 0, 4, s));
     HYDRA_HIP(hipStreamSynchronize(s));
+    return HYDRA_OK;
+}
+
+int hydra_layer_kernel_info(const hydra_ctx *c, int B, int64_t *info) {
+    if (!c || !info) return fail(HYDRA_E_INVALID_ARG, "hydra_layer_kernel_info: NULL argument");
+    if (B < 1 || B > c->max_batch) return fail(HYDRA_E_CAPACITY, "B outside [1, max_batch]");
+    int64_t v[4];
+    layers_mega_info(c, B, v);
+    const WsLayout w = ws_layout(c, B);
+    info[0] = v[0];
+    info[1] = v[0] ? (int64_t)(w.mega + v[1]) : 0;
+    info[2] = v[2];
+    info[3] = v[3];
     return HYDRA_OK;
 }
 
@@ -430,6 +451,17 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
         const int Mpad = (int)align_up(std::max<size_t>(M, 1), 128);
         RowScale rs = {ss, 1, Mpad, d, c->m.rms_eps};        // rs.nb: rows of ss the last producer filled (1 = a complete sum per row)
         const float *gain0 = (const float *)(A + c->layer[0].attn_norm);
+        if (lm_tail && src.tokens && layers_mega_eligible(c, B, kv)) {
+            // up to 64 rows and a bounded context: all layers in one persistent kernel (bf16_layers.hip)
+            LayersMegaIO io;
+            if ((rc = launch_layers_mega(c, s, B, W + w.mega, seq_len, kv, flags, &io, false))) return rc;
+            if ((rc = launch_embed_prep(c, s, src.tokens, io.x_first, gain0, io.xg_first, io.ss_first, io.Mpad, M, flags))) return rc;
+            if ((rc = launch_layers_mega(c, s, B, W + w.mega, seq_len, kv, flags, &io, true))) return rc;
+            const RowScale rl = {io.ss_last, io.nb_last, io.Mpad, d, c->m.rms_eps};
+            if ((rc = launch_final_hidden(c, s, io.x_last, (const float *)(A + c->off_final_norm), rl, hidden, M))) return rc;
+            if ((rc = launch_gemm(c, s, io.xg_last, A + c->off_lm_head, part, M, V, d, &p))) return rc;
+            return launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rl, M, argmax, margin, logits);
+        }
         if (src.tokens) { if ((rc = launch_embed_prep(c, s, src.tokens, x, gain0, xa, ss, Mpad, M, flags))) return rc; }
         else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, gain0, xa, ss, Mpad, flags))) return rc; }
         for (int l = 0; l < c->m.n_layers; ++l) {

@@ -116,8 +116,38 @@ __device__ __forceinline__ float part_sum(const float *part, int S, size_t split
     return a;
 }
 
+// ---- stores whose result another workgroup of the SAME kernel reads --------------------------------
+// The L2 caches of the chip's dies are not kept coherent with each other while a kernel runs.  A value that a
+// workgroup on another die reads after a grid-wide hand-off is therefore written with a device-scope store, which
+// goes through to memory (DEV = true); DEV = false is an ordinary store.  The reader must not have touched the
+// line earlier in the same kernel (the layer kernel gives every such buffer its own address per layer and stage).
+template <bool DEV, typename T>
+__device__ __forceinline__ void st_dev(T *p, T v) {
+    if (DEV) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool DEV>
+__device__ __forceinline__ void st_dev64(void *p, uint32_t lo, uint32_t hi) {
+    typedef __attribute__((ext_vector_type(2))) uint32_t u2;
+    if (DEV) __hip_atomic_store(reinterpret_cast<uint64_t *>(p), ((uint64_t)hi << 32) | lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *reinterpret_cast<u2 *>(p) = u2{lo, hi};
+}
+// 16 bytes as two 8-byte stores.  The elements are copied into named scalars first: a bit-cast applied directly to
+// an element of the vector was compiled (hipcc 7.2) into reads of element 0 for every element.
+template <bool DEV>
+__device__ __forceinline__ void st_dev128(void *p, __attribute__((ext_vector_type(4))) uint32_t v) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+    if (DEV) {
+        const uint32_t e0 = v[0], e1 = v[1], e2 = v[2], e3 = v[3];
+        st_dev64<true>(p, e0, e1);
+        st_dev64<true>(reinterpret_cast<char *>(p) + 8, e2, e3);
+    } else {
+        *reinterpret_cast<u4 *>(p) = v;
+    }
+}
+
 __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
-enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4 };
+enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4, FLAG_TIMEOUT = 8 };
 
 }  // namespace hydra

@@ -66,6 +66,7 @@ struct hydra_ctx {
     std::vector<hydra::HeadOff> head;   // index 1..K
     char *arena;                        // device, caller-owned
     int table_slot;
+    int n_cus;                          // compute units of the device (workgroups of the persistent layer kernel)
     // profiling
     bool profiling;
     std::vector<hipEvent_t> ev;
@@ -96,7 +97,7 @@ inline int    ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---- workspace ------------------------------------------------------------
 struct WsLayout {
-    size_t flags, x, xa, xb, part, qbuf, apart, z, ss, topk, total;
+    size_t flags, x, xa, xb, part, qbuf, apart, z, ss, topk, mega, total;
     int attn_units;     // split-KV units per (row, head, query group)
 };
 WsLayout ws_layout(const hydra_ctx *c, int B);
@@ -127,6 +128,15 @@ int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void 
 int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
                       float *ss, int Mpad, int M, int32_t *flags);
 int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float *gain, RowScale rs, float *hidden, int M);
+
+// The decoder layers as one persistent kernel (bf16_layers.hip), for forward passes of up to 64 rows.
+struct LayersMegaIO { float *x_first; void *xg_first; float *ss_first; float *x_last; void *xg_last; float *ss_last; int nb_last, Mpad; };
+size_t layers_mega_ws_bytes(const hydra_ctx *c, int B);
+bool layers_mega_eligible(const hydra_ctx *c, int B, const hydra_kv *kv);
+int layers_mega_set_attr(hydra_ctx *c);
+void layers_mega_info(const hydra_ctx *c, int B, int64_t *out);
+int launch_layers_mega(hydra_ctx *c, hipStream_t s, int B, char *mega, const int32_t *seq_len, const hydra_kv *kv, int32_t *flags,
+                       LayersMegaIO *io, bool launch);
 
 // packing (arena loads)
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K,

@@ -50,3 +50,15 @@ def test_attention_spills_stay_small():
     assert len(rep) >= 2
     for k, v in rep.items():
         assert v.get("spill", 0) <= 16, f"{k}: {v}"
+
+
+def test_layer_kernel_keeps_its_streams_in_registers():
+    """The persistent layer kernel: the instantiations for 64-wide heads must not use scratch memory at all; with
+    128-wide heads the attention step (which is at the register limit as a stand-alone kernel too) may spill, but the
+    weight-streaming loops may not: their spills showed up as several hundred spilled registers before the register
+    sets were shared between the steps."""
+    rep = {k: v for k, v in _resource_report("bf16_layers.hip").items() if "layers_kernel" in k}
+    assert len(rep) == 4
+    for k, v in rep.items():
+        limit = 0 if "ELi64EEE" in k else 140
+        assert v.get("spill", 0) <= limit, f"{k}: {v}"
