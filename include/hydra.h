@@ -248,6 +248,18 @@ int accept_typical(hydra_ctx *ctx, void *stream, int B, void *ws,
                    float tau, float eps, float alpha, const float *u,
                    int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
 
+/* accept_typical for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments (without ws), same results.
+ * The per-candidate pass flags live in a fixed buffer of 64 KiB inside the library (one per GPU, kept until the
+ * process ends; its address is looked up at hydra_bind_weights), which limits a call to B * T <= 16384 tree
+ * nodes: beyond that the call returns HYDRA_E_CAPACITY and does nothing.  The call itself allocates nothing.
+ * All calls on one GPU share that buffer: calls that overlap in time on one GPU (different streams or threads)
+ * race and must be serialised by the caller.  The buffer keeps the last call's contents; every entry a call
+ * reads is written by that call first. */
+int accept_typical_static(hydra_ctx *ctx, void *stream, int B,
+                          const int32_t *tree_tokens, const float *logits, float tau, float eps, float alpha,
+                          const float *u, int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
+
 /* Keeps the accepted tokens.  Per row, every layer, j = 0..n_acc-1: K/V slot
  * seq_len + path[j] -> slot seq_len + j (in place; sources are read before any
  * destination is written).  Then h_last[b] = hidden[b, last_node[b]],

@@ -24,7 +24,7 @@ E_INVALID_ARG, E_SHAPE, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_STATE = -1, -2, -3, 
 
 EXPORTS = ["hydra_create", "hydra_destroy", "hydra_last_error", "hydra_weights_bytes", "hydra_bind_weights",
            "hydra_load_tensor", "hydra_workspace_bytes", "hydra_read_flags", "hydra_draft_tree",
-           "tree_verify_forward", "tree_attention", "accept_greedy", "accept_typical", "kv_compact", "hydra_prefix_attention", "hydra_tree_depth",
+           "tree_verify_forward", "tree_attention", "accept_greedy", "accept_typical", "accept_typical_static", "kv_compact", "hydra_prefix_attention", "hydra_tree_depth",
            "hydra_kv_write", "hydra_kv_read", "hydra_profile_begin", "hydra_profile_end", "hydra_layer_kernel_info"]
 
 
@@ -73,6 +73,7 @@ def _load() -> C.CDLL:
     lib.tree_attention.argtypes = [vp, vp, i32, i32, vp, vp, vp, C.POINTER(KVDesc), vp]
     lib.accept_greedy.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.accept_typical.argtypes = [vp, vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_float, vp, vp, vp, vp, vp]
+    lib.accept_typical_static.argtypes = [vp, vp, i32, vp, vp, C.c_float, C.c_float, C.c_float, vp, vp, vp, vp, vp]
     lib.kv_compact.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, C.POINTER(KVDesc), vp, vp, vp, vp]
     lib.hydra_prefix_attention.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, C.POINTER(KVDesc), vp]
     lib.hydra_tree_depth.argtypes = [vp]
@@ -204,6 +205,13 @@ class Hydra:
                                    _ptr(u, torch.float32, "u"), _ptr(n_acc, torch.int32, "n_acc"),
                                    _ptr(path, torch.int32, "path"), _ptr(next_root, torch.int32, "next_root"),
                                    _ptr(last_node, torch.int32, "last_node")))
+
+    def accept_typical_static(self, B, tree_tokens, logits, tau, eps, alpha, u, n_acc, path, next_root, last_node) -> None:
+        _check(_lib.accept_typical_static(self._h, _stream(), B, _ptr(tree_tokens, torch.int32, "tree_tokens"),
+                                          _ptr(logits, torch.float32, "logits"), float(tau), float(eps), float(alpha),
+                                          _ptr(u, torch.float32, "u"), _ptr(n_acc, torch.int32, "n_acc"),
+                                          _ptr(path, torch.int32, "path"), _ptr(next_root, torch.int32, "next_root"),
+                                          _ptr(last_node, torch.int32, "last_node")))
 
     def kv_compact(self, B, n_acc, path, next_root, last_node, hidden, kv: KV, seq_len, h_last, root, kv_index=None) -> None:
         d = kv.desc()

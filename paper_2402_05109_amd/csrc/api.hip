@@ -261,6 +261,11 @@ int hydra_bind_weights(hydra_ctx *c, void *stream, void *arena, int table_slot) 
     HYDRA_HIP(hipMemcpyAsync(slot, &c->tree, sizeof(TreeDev), hipMemcpyHostToDevice, s));
     HYDRA_HIP(hipMemcpyAsync(c->arena + c->off_rope, c->rope.data(), c->rope.size() * 4, hipMemcpyHostToDevice, s));
     HYDRA_HIP(hipStreamSynchronize(s));     // host buffers may change after return
+    {   // set-up of accept_typical_static: the current device's address of its fixed buffer
+        int32_t *unused = nullptr;
+        int rc = typical_static_scratch(&unused);
+        if (rc) return rc;
+    }
     if (c->bf16) {
         int rc = gemm_max_dynamic_lds(c);
         if (rc) return rc;

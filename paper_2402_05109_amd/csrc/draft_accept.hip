@@ -548,4 +548,53 @@ int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, con
     return HYDRA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// accept_typical for callers that cannot allocate or pass a workspace (HIP graph capture, tight serving loops):
+// the per-candidate pass flags that typical_stats_kernel hands to typical_select_kernel live in a fixed array
+// in device memory that belongs to the library.  Each GPU has its own copy of the array at its own address; the
+// address is looked up once per device (scratch_pointer) and only that pointer is ever given to kernels or
+// memory calls, never the array's name.
+// ---------------------------------------------------------------------------
+enum { TYP_STATIC_MAX_NODES = 16384, TYP_MAX_DEVICES = 64 };          // B * T <= 16384: 64 KiB per device
+static __device__ __align__(256) int32_t scratch[TYP_STATIC_MAX_NODES];
+static int32_t *g_scratch_ptr[TYP_MAX_DEVICES];                        // per device; NULL until looked up
+
+// the current device's copy of `scratch`; looked up on first use on that device (hydra_bind_weights does it at set-up)
+int typical_static_scratch(int32_t **out) {
+    int dev = -1;
+    HYDRA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= TYP_MAX_DEVICES) return fail(HYDRA_E_UNSUPPORTED, "accept_typical_static: device index beyond 63");
+    int32_t *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void *sym = nullptr;
+        HYDRA_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym) return fail(HYDRA_E_HIP, "accept_typical_static: no device address for the scratch array");
+        p = static_cast<int32_t *>(sym);
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);    // every thread that races here stores the same address
+    }
+    *out = p;
+    return HYDRA_OK;
+}
+
 }  // namespace hydra
+
+extern "C" int accept_typical_static(hydra_ctx *c, void *stream, int B, const int32_t *tree_tokens, const float *logits, float tau,
+                                     float eps, float alpha, const float *u, int32_t *n_acc, int32_t *path, int32_t *next_root,
+                                     int32_t *last_node) {
+    using namespace hydra;
+    if (!c) return fail(HYDRA_E_INVALID_ARG, "ctx is NULL");
+    if (B < 1 || B > c->max_batch) return fail(HYDRA_E_CAPACITY, "B outside [1, max_batch]");
+    if (!c->arena) return fail(HYDRA_E_STATE, "no weight arena bound (hydra_bind_weights)");
+    if (!tree_tokens || !logits || !n_acc || !path || !next_root || !last_node)
+        return fail(HYDRA_E_INVALID_ARG, "accept_typical_static: NULL argument");
+    if (!(tau > 0.f) || !(eps >= 0.f) || !(alpha >= 0.f)) return fail(HYDRA_E_INVALID_ARG, "accept_typical_static: need tau > 0, eps >= 0, alpha >= 0");
+    if ((int64_t)B * c->tree.T > TYP_STATIC_MAX_NODES)
+        return fail(HYDRA_E_CAPACITY, "accept_typical_static: B * T exceeds the 16384 tree nodes its fixed buffer holds; use accept_typical with a workspace");
+    int32_t *ok = nullptr;
+    int rc = typical_static_scratch(&ok);
+    if (rc) return rc;
+    int32_t *flags = reinterpret_cast<int32_t *>(c->arena + c->off_tables + (size_t)c->table_slot * TABLE_SLOT_BYTES + FLAGS_OFF_IN_SLOT);
+    // typical_stats_kernel writes the flag of every non-root node before typical_select_kernel reads it, so nothing
+    // in the buffer has to start at zero
+    return launch_accept_typical(c, (hipStream_t)stream, B, tree_tokens, logits, tau, eps, alpha, u, ok, flags, n_acc, path, next_root, last_node);
+}

@@ -181,6 +181,7 @@ int launch_accept(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens
 int launch_accept_typical(hydra_ctx *c, hipStream_t s, int B, const int32_t *tree_tokens, const float *logits, float tau,
                           float eps, float alpha, const float *u, int32_t *ok_scratch, int32_t *flags, int32_t *n_acc,
                           int32_t *path, int32_t *next_root, int32_t *last_node);
+int typical_static_scratch(int32_t **out);       // the current device's copy of accept_typical_static's fixed buffer
 int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, const int32_t *path,
                    const int32_t *next_root, const int32_t *last_node, const float *hidden, const hydra_kv *kv,
                    int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index);
