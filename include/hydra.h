@@ -42,6 +42,13 @@
  *     dtype HYDRA_BF16: weights are given as bfloat16; the KV cache holds 16-bit
  *     elements and GEMM inputs are rounded to 16 bits (the library keeps these
  *     as IEEE half, in which bfloat16 weights are exact); all sums are fp32.
+ *     Supported range of that 16-bit interior: weights of magnitude >= 2^-17
+ *     are exact, smaller ones lose low bits and below 2^-25 become zero (flag
+ *     bit 5 at load time); GEMM inputs are the residual stream times the norm
+ *     gain BEFORE the division by its rms (the division commutes with the
+ *     contraction and is applied afterwards), so |x * gain| must stay within
+ *     65504, as must q, k, v and the SwiGLU activations; a value beyond that is
+ *     clamped and flag bit 4 is raised (hydra_read_flags), never silently.
  *     In both, h_last / hidden / logits / margin are fp32 and token ids,
  *     lengths and indices are int32.
  */
@@ -180,10 +187,16 @@ size_t hydra_workspace_bytes(const hydra_ctx *ctx, int B);
  * this function (or since hydra_bind_weights): bit 0 = a row's seq_len + T
  * exceeded its page table or max_pos (row skipped), bit 1 = a token id outside
  * [0, V) (treated as 0), bit 2 = hydra_prefix_attention met an n_acc outside
- * [1, P] or a path entry outside [0, T_src) (clamped), bit 3 = a bounded wait
+ * [1, P] or a path entry outside [0, T_src) (clamped), or kv_compact met a path
+ * that is not strictly increasing inside [0, T) (the copies stop there),
+ * bit 3 = a bounded wait
  * inside the persistent layer kernel expired (see hydra_layer_kernel_info; the
- * outputs of that call are undefined).  Reads and clears them; synchronises the
- * stream. */
+ * outputs of that call are undefined), bit 4 = a value that feeds a GEMM or the
+ * cache of the bf16 family exceeded the largest finite half (65504) and was
+ * clamped, bit 5 = hydra_load_tensor met a non-zero bfloat16 weight too small
+ * for the 16-bit interior (|w| < 2^-25: stored as zero), bit 6 = a page-table
+ * entry outside [0, n_pages) (the row's K/V are not written, reads use page 0,
+ * copies are skipped).  Reads and clears them; synchronises the stream. */
 int hydra_read_flags(hydra_ctx *ctx, void *stream, int32_t *flags_out /* host */);
 
 /* ---- the hot path -------------------------------------------------------- */
@@ -212,7 +225,8 @@ int tree_verify_forward(hydra_ctx *ctx, void *stream, int B, void *ws,
                         const int32_t *tree_tokens, const int32_t *seq_len, const hydra_kv *kv,
                         float *hidden, int32_t *argmax, float *margin, float *logits);
 
-/* The attention of one layer of tree_verify_forward on its own:
+/* Section 2 ("Tree decoding": every node attends to the verified prefix, its
+ * ancestors and itself).  The attention of one layer of tree_verify_forward on its own:
  *   q   device [B, T, H, Dh] fp32, already rotated
  *   out device [B, T, H, Dh] fp32
  * K/V of the T nodes must already be in slots seq_len[b] .. seq_len[b]+T-1
@@ -260,10 +274,17 @@ int accept_typical_static(hydra_ctx *ctx, void *stream, int B,
                           const int32_t *tree_tokens, const float *logits, float tau, float eps, float alpha,
                           const float *u, int32_t *n_acc, int32_t *path, int32_t *next_root, int32_t *last_node);
 
-/* Keeps the accepted tokens.  Per row, every layer, j = 0..n_acc-1: K/V slot
+/* Sections 1 and 2 (speculative decoding: the accepted tokens are appended to the
+ * sequence, the rest of the candidates is discarded; section 3: the next step's
+ * heads read the hidden state of the last accepted token).
+ * Keeps the accepted tokens.  Per row, every layer, j = 0..n_acc-1: K/V slot
  * seq_len + path[j] -> slot seq_len + j (in place; sources are read before any
  * destination is written).  Then h_last[b] = hidden[b, last_node[b]],
- * root[b] = next_root[b], seq_len[b] += n_acc[b].
+ * root[b] = next_root[b], seq_len[b] += n_acc[b].  A row that tree_verify_forward
+ * skipped for lack of page-table capacity keeps its seq_len, h_last and root (its
+ * kv_index is -1).  path must be strictly increasing with path[j] >= j (what
+ * accept_greedy and accept_typical produce); otherwise the copies stop at the
+ * offending entry and flag bit 2 is raised.
  *   kv_index device [B, Dmax+1, 2] int32 (out) or NULL: (physical page, offset
  *   in page) written for each j, -1 padded.                                     */
 int kv_compact(hydra_ctx *ctx, void *stream, int B,

@@ -78,7 +78,7 @@ __device__ __forceinline__ void attn_bf16_body(
 #pragma unroll
         for (int j = 0; j < PG_AHEAD; ++j) {
             const int t = unit + j * units;
-            pg[j][0] = pt[min(2 * t, max_pages - 1)];
+            pg[j][0] = pt[min(2 * t, max_pages - 1)];             // checked below, where they are used
             pg[j][1] = pt[min(2 * t + 1, max_pages - 1)];
         }
     }
@@ -101,7 +101,11 @@ __device__ __forceinline__ void attn_bf16_body(
     if (active && unit < n_tiles) {
         KVTile<DH> cur, nxt;
         // second page of a tile: absent when the row ends inside the first one (its keys are masked; any valid page will do)
-        load_kv_tile<DH>(cur, kpages, vpages, pg[0][0], (2 * unit + 1 < row_pages) ? pg[0][1] : pg[0][0], layer, n_pages, H, h, lane);
+        {
+            const int p0 = checked_page(pg[0][0], n_pages, flags);
+            const int p1 = (2 * unit + 1 < row_pages) ? checked_page(pg[0][1], n_pages, flags) : p0;
+            load_kv_tile<DH>(cur, kpages, vpages, p0, p1, layer, n_pages, H, h, lane);
+        }
         int it = 0;                                        // index of tile t among this wave's tiles
         for (int t = unit; t < n_tiles; t += units, ++it) {
             const bool more = t + units < n_tiles;
@@ -116,6 +120,8 @@ __device__ __forceinline__ void attn_bf16_body(
                     default: p0 = pt[2 * tn]; p1 = (2 * tn + 1 < row_pages) ? pt[2 * tn + 1] : p0; break;
                 }
                 if (2 * tn + 1 >= row_pages) p1 = p0;
+                p0 = checked_page(p0, n_pages, flags);                  // wave-uniform
+                p1 = checked_page(p1, n_pages, flags);
                 load_kv_tile<DH>(nxt, kpages, vpages, p0, p1, layer, n_pages, H, h, lane);
             }
             const int slot0 = t * 32;

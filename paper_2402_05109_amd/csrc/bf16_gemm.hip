@@ -212,7 +212,7 @@ int launch_gemm(hydra_ctx *c, hipStream_t s, const void *X, const void *W, float
 __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, const float *__restrict__ part, int S,
                                                           int ld, size_t split_stride, const float *__restrict__ gain,
                                                           a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad,
-                                                          int d) {
+                                                          int d, int32_t *flags) {
     __shared__ float red[4];
     const int m = blockIdx.y;
     const int k = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -230,8 +230,8 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *__restrict__ x, 
                 if (s0 + u < S) { a[0] += q[u][0]; a[1] += q[u][1]; a[2] += q[u][2]; a[3] += q[u][3]; }
         }
         *reinterpret_cast<f32x4_t *>(x + (size_t)m * d + k) = a;
-        const uint32_t lo = f2a_pack(a[0] * gn[0], a[1] * gn[1]);
-        const uint32_t hi = f2a_pack(a[2] * gn[2], a[3] * gn[3]);
+        const uint32_t lo = f2a_pack_f(a[0] * gn[0], a[1] * gn[1], flags);
+        const uint32_t hi = f2a_pack_f(a[2] * gn[2], a[3] * gn[3], flags);
         uint32_t *dst = reinterpret_cast<uint32_t *>(xg + x_index<true>(m, k, d));     // 4 consecutive k share an 8-run
         dst[0] = lo; dst[1] = hi;
         sq = a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
@@ -252,28 +252,28 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
         int rc = launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, N, K, p, epi);
         if (rc) return rc;
         hipLaunchKernelGGL(resid_norm_kernel, dim3(ceil_div(N, 1024), M), dim3(256), 0, s, x, part, p.splits, npad, stride,
-                           gain, (a16_t *)xg, ss, Mpad, N);
+                           gain, (a16_t *)xg, ss, Mpad, N, flags_dev(c));
         HYDRA_LAUNCH_CHECK("resid_norm_kernel");
         *ss_bands = ceil_div(N, 1024);       // one partial sum per 1024-column chunk
         return HYDRA_OK;
     }
     *ss_bands = N / 32;                      // the fused epilogue leaves one partial sum per 32-column band
     p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
-    EpiResid epi{x, N, gain, (a16_t *)xg, ss, Mpad};
+    EpiResid epi{x, N, gain, (a16_t *)xg, ss, Mpad, flags_dev(c)};
     return launch_bf16<EpiResid, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act) {
     GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_SWIGLU);
-    EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (a16_t *)act, F};
+    EpiSilu epi{ss, nb, Mpad, K, c->m.rms_eps, (a16_t *)act, F, flags_dev(c)};
     return launch_bf16<EpiSilu, NT_ANY>(c, s, X, W, M, 2 * F, K, p, epi);
 }
 
 int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K,
                           const float *bias, float *z, bool residual, void *xg) {
     GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
-    EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (a16_t *)xg};
+    EpiBiasSilu epi{bias, z, N, residual ? 1 : 0, (a16_t *)xg, flags_dev(c)};
     return launch_bf16<EpiBiasSilu, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
@@ -338,7 +338,7 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
 // 16-byte lane entry.
 // ---------------------------------------------------------------------------
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__restrict__ dst, int N, int K,
-                                   int tile_off, int tile_stride, int rows_per_band, int col_off, int bph) {
+                                   int tile_off, int tile_stride, int rows_per_band, int col_off, int bph, int32_t *flags) {
     const int KT = K >> 4;
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // (band, kt, lane)
     const int nbands = (N + rows_per_band - 1) / rows_per_band;
@@ -355,8 +355,12 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__re
     if (n < N) {
         const u32x4_t raw = *reinterpret_cast<const u32x4_t *>(src + (size_t)n * K + k);     // 8 bfloat16
 #pragma unroll
-        for (int q = 0; q < 4; ++q)                                                          // -> 8 half (exact from 2^-17 up)
+        for (int q = 0; q < 4; ++q) {                                                        // -> 8 half (exact from 2^-17 up)
             v[q] = f2a_pack(__uint_as_float(raw[q] << 16), __uint_as_float(raw[q] & 0xffff0000u));
+            // a non-zero weight below 2^-25 becomes zero in half: reported (flag bit 5), not silent
+            const bool lost = ((raw[q] & 0x7fffu) != 0u && (v[q] & 0x7fffu) == 0u) || ((raw[q] & 0x7fff0000u) != 0u && (v[q] & 0x7fff0000u) == 0u);
+            if (lost) atomicOr(flags, FLAG_WEIGHT_UNDERFLOW);
+        }
     }
     int dband = band;
     if (bph > 1) {                      // rotary pairing: bands o and o + bph/2 of a head become neighbours
@@ -368,10 +372,9 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, u32x4_t *__re
 
 int launch_pack_matrix(hydra_ctx *c, hipStream_t s, const void *src, void *dst, int N, int K, int tile_off,
                        int tile_stride, int rows_per_band, int col_off, int bph) {
-    (void)c;
     const size_t total = (size_t)ceil_div(N, rows_per_band) * (K / 16) * 64;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)src,
-                       (u32x4_t *)dst, N, K, tile_off, tile_stride, rows_per_band, col_off, bph);
+                       (u32x4_t *)dst, N, K, tile_off, tile_stride, rows_per_band, col_off, bph, flags_dev(c));
     HYDRA_LAUNCH_CHECK("pack_weight_kernel");
     return HYDRA_OK;
 }

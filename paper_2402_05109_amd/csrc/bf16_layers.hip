@@ -368,7 +368,7 @@ __device__ __forceinline__ void gemm_stage(const GemmGeom &g, const Epilogue &ep
 // over the 1024-column chunk.  One half workgroup (256 threads) per (row, chunk).
 __device__ __forceinline__ void resid_stage(const float *__restrict__ part, int S, size_t split_stride, int ld,
                                             const float *__restrict__ x_in, float *__restrict__ x_out, const float *__restrict__ gain,
-                                            a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad, int M, int d, float *lds) {
+                                            a16_t *__restrict__ xg, float *__restrict__ ss, int Mpad, int M, int d, float *lds, int32_t *flags) {
     const int tix = opaque_tid();
     const int half = tix >> 8, tid = tix & 255, wave = tix >> 6;
     const int n_chunks = (d + 1023) >> 10, n_units = M * n_chunks;
@@ -393,7 +393,7 @@ __device__ __forceinline__ void resid_stage(const float *__restrict__ part, int 
             float *xo = x_out + (size_t)m * d + k;
             st_dev64<true>(xo, __float_as_uint(a[0]), __float_as_uint(a[1]));
             st_dev64<true>(xo + 2, __float_as_uint(a[2]), __float_as_uint(a[3]));
-            st_dev64<true>(xg + x_index<true>(m, k, d), f2a_pack(a[0] * gn[0], a[1] * gn[1]), f2a_pack(a[2] * gn[2], a[3] * gn[3]));
+            st_dev64<true>(xg + x_index<true>(m, k, d), f2a_pack_f(a[0] * gn[0], a[1] * gn[1], flags), f2a_pack_f(a[2] * gn[2], a[3] * gn[3], flags));
             sq = a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
         }
         sq = wave_sum(sq);
@@ -510,7 +510,7 @@ __global__ __launch_bounds__(LK_THREADS) void layers_kernel(LayerKernelArgs A) {
         lk_stamp(A, l, 3, 0);
         ++bar;
         // ---- residual + norm input of the FFN
-        resid_stage(part_o, A.o.splits, part_stride, npad_d, x_in, x_a, gain_ffn, xg_a, ss_a, A.Mpad, A.M, d, lds);
+        resid_stage(part_o, A.o.splits, part_stride, npad_d, x_in, x_a, gain_ffn, xg_a, ss_a, A.Mpad, A.M, d, lds, A.flags);
         lk_stamp(A, l, 3, 1);
         gs_arrive(A.sync, bar, ctl);
         lk_stamp(A, l, 3, 2);
@@ -523,7 +523,7 @@ __global__ __launch_bounds__(LK_THREADS) void layers_kernel(LayerKernelArgs A) {
         {
             GemmGeom g;
             g.X = reinterpret_cast<const u32x4_t *>(xg_a); g.W = nullptr; g.M = A.M; g.NTiles = bands_g; g.KT = KTd; g.kpw = 0; g.NW = 1; g.KW = LK_WAVES;
-            EpiSiluT<true> epi{ss_a, A.nb, A.Mpad, d, A.eps, act, F};
+            EpiSiluT<true> epi{ss_a, A.nb, A.Mpad, d, A.eps, act, F, A.flags};
             gemm_stage<MB, S::NT_G, S::U_G>(g, epi, wg, r, lds, Prefetch<S::NT_D, S::U_D>{r, wd}, lk_stamp_ptr(A, l, 4));
         }
         lk_stamp(A, l, 4, 1);
@@ -552,7 +552,7 @@ __global__ __launch_bounds__(LK_THREADS) void layers_kernel(LayerKernelArgs A) {
         lk_stamp(A, l, 6, 0);
         ++bar;
         // ---- residual + norm input of the next layer (or of the LM head)
-        resid_stage(part_d, A.dn.splits, part_stride, npad_d, x_a, x_b, gain_next, xg_b, ss_b, A.Mpad, A.M, d, lds);
+        resid_stage(part_d, A.dn.splits, part_stride, npad_d, x_a, x_b, gain_next, xg_b, ss_b, A.Mpad, A.M, d, lds, A.flags);
         lk_stamp(A, l, 6, 1);
         if (l + 1 < A.NL) {
             gs_arrive(A.sync, bar, ctl);

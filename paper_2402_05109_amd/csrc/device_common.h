@@ -41,6 +41,14 @@ __device__ __forceinline__ uint32_t f2a_pack(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h16x2_));
 }
 __device__ __forceinline__ float a2f(a16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+// The same conversions for values that feed a GEMM or the cache: a value beyond the largest finite half is still
+// clamped, but the clamp is reported (flag bit 4), so a residual stream with channels too large for the 16-bit
+// interior never passes silently.
+__device__ __forceinline__ void flag_saturation(float a, float b, int32_t *flags) {
+    if (fmaxf(fabsf(a), fabsf(b)) > 65504.f) atomicOr(flags, 16 /* FLAG_SATURATED */);
+}
+__device__ __forceinline__ a16_t f2a_f(float f, int32_t *flags) { flag_saturation(f, 0.f, flags); return f2a(f); }
+__device__ __forceinline__ uint32_t f2a_pack_f(float lo, float hi, int32_t *flags) { flag_saturation(lo, hi, flags); return f2a_pack(lo, hi); }
 
 template <bool BF> struct Elem;
 template <> struct Elem<true>  { typedef bf16_t type; static __device__ __forceinline__ float ld(const bf16_t *p, size_t i) { return bf2f(p[i]); }
@@ -85,6 +93,13 @@ template <bool BF> __device__ __forceinline__ int v_in_block(int tok, int dim, i
 }
 __device__ __forceinline__ size_t kv_block_base(int layer, int n_pages, int page, int H, int head, int Dh) {
     return ((((size_t)layer * n_pages + page) * H) + head) * (size_t)(16 * Dh);
+}
+
+// A page id from the caller's page table: ids outside [0, n_pages) are reported (flag bit 6) and replaced by page 0,
+// so that a bad table entry gives a flagged wrong result instead of an access outside the cache.
+__device__ __forceinline__ int checked_page(int page, int n_pages, int32_t *flags) {
+    if ((unsigned)page >= (unsigned)n_pages) { atomicOr(flags, 64 /* FLAG_BAD_PAGE */); return 0; }
+    return page;
 }
 
 // ---- wave reductions (64 lanes) ------------------------------------------------
@@ -148,6 +163,6 @@ __device__ __forceinline__ void st_dev128(void *p, __attribute__((ext_vector_typ
 
 __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
-enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4, FLAG_TIMEOUT = 8 };
+enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4, FLAG_TIMEOUT = 8, FLAG_SATURATED = 16, FLAG_WEIGHT_UNDERFLOW = 32, FLAG_BAD_PAGE = 64 };
 
 }  // namespace hydra

@@ -118,11 +118,10 @@ int launch_bias_silu(hydra_ctx *c, hipStream_t s, const float *part, int S, int 
 
 // ---------------------------------------------------------------------------
 // Top-k per row, ordered by (logit descending, token id ascending) (paper,
-// section 2: children are the m most likely tokens, sorted).
-// One workgroup of 16 waves per row.  Each lane keeps up to 32 logits in
-// registers; every wave extracts its own k best with k rounds of a wave-wide
-// reduction (no workgroup barrier), the 16 x k survivors go to LDS and wave 0
-// extracts the final k from them the same way.
+// section 2: children are the m most likely tokens, sorted).  The helpers come
+// first (order, monotone keys, wave-wide reductions); the two kernels that use
+// them, one wave per 1024-id chunk and one wave per row for the merge, are
+// described above topk_chunk_kernel.
 // ---------------------------------------------------------------------------
 struct Cand { float v; int id; };
 __device__ __forceinline__ bool better(float v, int id, float w, int jd) { return v > w || (v == w && id < jd); }
@@ -483,11 +482,15 @@ int launch_accept_typical(hydra_ctx *c, hipStream_t s, int B, const int32_t *tre
 // A thread owns one (layer, head, dim) element column and walks j upwards;
 // path[j] >= j and strictly increasing, so within a column every source is read
 // before it can be overwritten and no two threads touch the same element.
+// A path that is not strictly increasing inside [0, T) (only a caller's own
+// path can be: accept_greedy and accept_typical always produce one) ends the
+// walk at the offending entry and is reported (FLAG_BAD_PATH); page ids outside
+// the cache are reported (FLAG_BAD_PAGE) and their copies skipped.
 // ---------------------------------------------------------------------------
 template <bool BF>
 __global__ void compact_kernel(const TreeDev *tree, const int32_t *n_acc, const int32_t *path,
                                const int32_t *seq_len, const int32_t *page_table, int max_pages, int n_pages,
-                               typename Act<BF>::type *kpages, typename Act<BF>::type *vpages, int H, int Dh) {
+                               typename Act<BF>::type *kpages, typename Act<BF>::type *vpages, int H, int Dh, int32_t *flags) {
     const int h = blockIdx.x, layer = blockIdx.y, b = blockIdx.z;
     const int dim = threadIdx.x;
     if (dim >= Dh) return;
@@ -496,12 +499,23 @@ __global__ void compact_kernel(const TreeDev *tree, const int32_t *n_acc, const 
     const int plen = tree->max_depth + 1;
     int na = n_acc[b];
     na = na < 0 ? 0 : (na > plen ? plen : na);
+    int prev = -1;
     for (int j = 0; j < na; ++j) {
         const int n = path[(size_t)b * plen + j];
-        if (n == j || n < 0 || n >= tree->T) continue;
+        if (n <= prev || n < j || n >= tree->T) {          // the same for every thread of the row
+            if (dim == 0 && h == 0 && layer == 0) atomicOr(flags, FLAG_BAD_PATH);
+            break;
+        }
+        prev = n;
+        if (n == j) continue;
         const int ss = L + n, ds = L + j;
-        const size_t sb = kv_block_base(layer, n_pages, page_table[(size_t)b * max_pages + (ss >> 4)], H, h, Dh);
-        const size_t db = kv_block_base(layer, n_pages, page_table[(size_t)b * max_pages + (ds >> 4)], H, h, Dh);
+        const int sp = page_table[(size_t)b * max_pages + (ss >> 4)], dp = page_table[(size_t)b * max_pages + (ds >> 4)];
+        if ((unsigned)sp >= (unsigned)n_pages || (unsigned)dp >= (unsigned)n_pages) {
+            if (dim == 0 && h == 0 && layer == 0) atomicOr(flags, FLAG_BAD_PAGE);
+            continue;
+        }
+        const size_t sb = kv_block_base(layer, n_pages, sp, H, h, Dh);
+        const size_t db = kv_block_base(layer, n_pages, dp, H, h, Dh);
         kpages[db + k_in_block<BF>(ds & 15, dim, Dh)] = kpages[sb + k_in_block<BF>(ss & 15, dim, Dh)];
         vpages[db + v_in_block<BF>(ds & 15, dim, Dh)] = vpages[sb + v_in_block<BF>(ss & 15, dim, Dh)];
     }
@@ -509,6 +523,9 @@ __global__ void compact_kernel(const TreeDev *tree, const int32_t *n_acc, const 
 
 // h_last <- hidden[last accepted node]; root <- next_root; seq_len += n_acc;
 // kv_index[j] = (physical page, offset) of slot L + j.  Runs after compact_kernel.
+// A row that the verify kernels skipped for lack of cache capacity keeps its state
+// (seq_len, h_last, root) and gets kv_index = -1: its n_acc, last_node and hidden
+// were computed from nothing.
 __global__ void state_update_kernel(const TreeDev *tree, const int32_t *n_acc, const int32_t *next_root,
                                     const int32_t *last_node, const float *hidden, const int32_t *page_table,
                                     int max_pages, int d, int32_t *seq_len, float *h_last, int32_t *root,
@@ -516,23 +533,24 @@ __global__ void state_update_kernel(const TreeDev *tree, const int32_t *n_acc, c
     const int b = blockIdx.x;
     const int T = tree->T, plen = tree->max_depth + 1;
     const int L = seq_len[b];
+    const bool ok = L >= 0 && L + T <= max_pages * 16;     // uniform over the workgroup
     int na = n_acc[b];
     na = na < 0 ? 0 : (na > plen ? plen : na);
     int last = last_node[b];
     last = last < 0 ? 0 : (last >= T ? T - 1 : last);
-    for (int k = threadIdx.x; k < d; k += blockDim.x) h_last[(size_t)b * d + k] = hidden[((size_t)b * T + last) * d + k];
+    if (ok)
+        for (int k = threadIdx.x; k < d; k += blockDim.x) h_last[(size_t)b * d + k] = hidden[((size_t)b * T + last) * d + k];
     __syncthreads();                                        // every thread has read seq_len[b]
     if (threadIdx.x == 0) {
-        root[b] = next_root[b];
+        if (ok) root[b] = next_root[b];
         if (kv_index) {
-            const bool ok = L >= 0 && L + T <= max_pages * 16;
             for (int j = 0; j < plen; ++j) {
                 const bool in = ok && j < na;
                 kv_index[((size_t)b * plen + j) * 2 + 0] = in ? page_table[(size_t)b * max_pages + ((L + j) >> 4)] : -1;
                 kv_index[((size_t)b * plen + j) * 2 + 1] = in ? ((L + j) & 15) : -1;
             }
         }
-        seq_len[b] = L + na;
+        if (ok) seq_len[b] = L + na;
     }
 }
 
@@ -540,8 +558,8 @@ int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, con
                    const int32_t *next_root, const int32_t *last_node, const float *hidden, const hydra_kv *kv,
                    int32_t *seq_len, float *h_last, int32_t *root, int32_t *kv_index) {
     dim3 grid(c->m.n_heads, c->m.n_layers, B), block(c->m.head_dim);
-    if (c->bf16) hipLaunchKernelGGL(compact_kernel<true>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, c->m.n_heads, c->m.head_dim);
-    else         hipLaunchKernelGGL(compact_kernel<false>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (float *)kv->k_pages, (float *)kv->v_pages, c->m.n_heads, c->m.head_dim);
+    if (c->bf16) hipLaunchKernelGGL(compact_kernel<true>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, c->m.n_heads, c->m.head_dim, flags_dev(c));
+    else         hipLaunchKernelGGL(compact_kernel<false>, grid, block, 0, s, tree_dev(c), n_acc, path, seq_len, kv->page_table, kv->max_pages, kv->n_pages, (float *)kv->k_pages, (float *)kv->v_pages, c->m.n_heads, c->m.head_dim, flags_dev(c));
     HYDRA_LAUNCH_CHECK("compact_kernel");
     hipLaunchKernelGGL(state_update_kernel, dim3(B), dim3(256), 0, s, tree_dev(c), n_acc, next_root, last_node, hidden, kv->page_table, kv->max_pages, c->m.d, seq_len, h_last, root, kv_index);
     HYDRA_LAUNCH_CHECK("state_update_kernel");

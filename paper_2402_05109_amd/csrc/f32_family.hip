@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
         }
         float sc = -INFINITY;
         if (valid) {
-            const int page = page_table[(size_t)b * max_pages + (key >> 4)];
+            const int page = checked_page(page_table[(size_t)b * max_pages + (key >> 4)], n_pages, flags);
             const float *kp = kpages + kv_block_base(layer, n_pages, page, H, h, Dh) + (size_t)(key & 15) * Dh;
             float a = 0.f;
             for (int i = 0; i < Dh; ++i) a = fmaf(qs[i], kp[i], a);
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *__restrict__ 
             const float pk = __shfl(p, kk, 64);
             if (pk == 0.f) continue;                            // masked keys are never read
             const int ks = base + kk;
-            const int page = page_table[(size_t)b * max_pages + (ks >> 4)];
+            const int page = checked_page(page_table[(size_t)b * max_pages + (ks >> 4)], n_pages, flags);
             const float *vp = vpages + kv_block_base(layer, n_pages, page, H, h, Dh) + (size_t)(ks & 15) * Dh;
             if (lane < Dh) o0 = fmaf(pk, vp[lane], o0);
             if (lane + 64 < Dh) o1 = fmaf(pk, vp[lane + 64], o1);

@@ -104,7 +104,7 @@ struct EpiPlainT {
 // contraction and is applied by the consumer) and ss[band][row] = sum over the
 // band's 32 columns of x^2.
 struct EpiResid {
-    float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad;
+    float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad; int32_t *flags;
     static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
@@ -132,7 +132,7 @@ struct EpiResid {
             float sq = 0.f;
             if (row < g.M) {
                 xp[(size_t)row * d + col] = xn;
-                xgp[x_index<true>(row, col, d)] = f2a(xn * gn);
+                xgp[x_index<true>(row, col, d)] = f2a_f(xn * gn, flags);
                 sq = xn * xn;
             }
 #pragma unroll
@@ -149,7 +149,7 @@ struct EpiResid {
 // half rows v >= 8, each fetching the partner value from the lane 16 columns away.
 template <bool DEV>
 struct EpiSiluT {
-    const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F;
+    const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F; int32_t *flags;
     static constexpr bool LDS_PROLOGUE = true, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         return rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
@@ -184,7 +184,9 @@ struct EpiSiluT {
             const int vv = left ? v : v + 8;
             const int rl = 8 * (vv >> 2) + 4 * hl + (vv & 3);            // row inside the 32-row block
             const float r = left ? rstd[8 * (v >> 2) + (v & 3)] : rstd[8 * ((v + 8) >> 2) + (v & 3)];
-            stage[((fo >> 3) * 32 + rl) * 8 + (fo & 7)] = f2a(silu_f(r * gate) * (r * up));
+            const float y = silu_f(r * gate) * (r * up);
+            if ((t.mb0 + a) * 32 + rl < g.M) flag_saturation(y, 0.f, flags);     // rows past M hold don't-care values: not reported
+            stage[((fo >> 3) * 32 + rl) * 8 + (fo & 7)] = f2a(y);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");           // LDS is in order within a wave; keep the compiler from reordering
         __builtin_amdgcn_wave_barrier();
@@ -268,7 +270,12 @@ struct EpiQkvRopeT {
                 if (ok) {
                     const int slot = L + n;
                     c.pos[q] = L + p.dep[q];
-                    c.pagetok[q] = page_table[(size_t)b * max_pages + (slot >> 4)] * 16 + (slot & 15);
+                    const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
+                    if ((unsigned)page >= (unsigned)n_pages) {            // bad table entry: the row is skipped and flagged
+                        if (t.tile0 == 0) atomicOr(flags, FLAG_BAD_PAGE);
+                        c.pos[q] = -1;
+                    }
+                    c.pagetok[q] = page * 16 + (slot & 15);
                     c.bn[q] = b * 128 + n;
                 } else if (t.tile0 == 0) {
                     atomicOr(flags, FLAG_CAPACITY);
@@ -313,8 +320,8 @@ struct EpiQkvRopeT {
                 const float r = rstd[rl0 + q];
                 const size_t base = kv_block_base(layer, n_pages, pagetok[q] >> 4, H, h, Dh);
                 const int tok = pagetok[q] & 15;
-                st_dev<DEV>(vp + base + v_in_block<true>(tok, dim0, Dh), f2a(r * x0[q]));
-                st_dev<DEV>(vp + base + v_in_block<true>(tok, dim1, Dh), f2a(r * x1[q]));
+                st_dev<DEV>(vp + base + v_in_block<true>(tok, dim0, Dh), f2a_f(r * x0[q], flags));
+                st_dev<DEV>(vp + base + v_in_block<true>(tok, dim1, Dh), f2a_f(r * x1[q], flags));
             }
             return;
         }
@@ -335,14 +342,14 @@ struct EpiQkvRopeT {
                 const int b = bn[q] >> 7, n = bn[q] & 127;
                 const int QT = (T + 31) >> 5, KS = Dh >> 4;
                 const size_t blk = (((size_t)b * H + h) * QT + (n >> 5)) * KS;
-                st_dev<DEV>(qp + ((((blk + (j >> 4)) * 64 + ((j >> 3) & 1) * 32 + (n & 31)) << 3) + (j & 7)), f2a(y0));
+                st_dev<DEV>(qp + ((((blk + (j >> 4)) * 64 + ((j >> 3) & 1) * 32 + (n & 31)) << 3) + (j & 7)), f2a_f(y0, flags));
                 const int j1 = j + half;
-                st_dev<DEV>(qp + ((((blk + (j1 >> 4)) * 64 + ((j1 >> 3) & 1) * 32 + (n & 31)) << 3) + (j1 & 7)), f2a(y1));
+                st_dev<DEV>(qp + ((((blk + (j1 >> 4)) * 64 + ((j1 >> 3) & 1) * 32 + (n & 31)) << 3) + (j1 & 7)), f2a_f(y1, flags));
             } else {
                 const size_t base = kv_block_base(layer, n_pages, pagetok[q] >> 4, H, h, Dh);
                 const int tok = pagetok[q] & 15;
-                st_dev<DEV>(kp + base + k_in_block<true>(tok, j, Dh), f2a(y0));
-                st_dev<DEV>(kp + base + k_in_block<true>(tok, j + half, Dh), f2a(y1));
+                st_dev<DEV>(kp + base + k_in_block<true>(tok, j, Dh), f2a_f(y0, flags));
+                st_dev<DEV>(kp + base + k_in_block<true>(tok, j + half, Dh), f2a_f(y1, flags));
             }
         }
     }
@@ -352,7 +359,7 @@ struct EpiQkvRopeT {
 
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
-    const float *bias; float *z; int d; int residual; a16_t *xg;
+    const float *bias; float *z; int d; int residual; a16_t *xg; int32_t *flags;
     static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
@@ -377,7 +384,7 @@ struct EpiBiasSilu {
             if (row >= g.M) continue;
             const float y = silu_f(acc[v] + bv) + zo[v];
             zp[(size_t)row * d + col] = y;
-            xgp[x_index<true>(row, col, d)] = f2a(y);
+            xgp[x_index<true>(row, col, d)] = f2a_f(y, flags);
         }
     }
 };

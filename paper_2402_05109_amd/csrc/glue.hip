@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void embed_prep_kernel(const bf16_t *E, const 
         for (int q = 0; q < 4; ++q) { v[2 * q] = __uint_as_float(raw[q] << 16); v[2 * q + 1] = __uint_as_float(raw[q] & 0xffff0000u); }
         *reinterpret_cast<f4 *>(x + (size_t)m * d + k) = f4{v[0], v[1], v[2], v[3]};
         *reinterpret_cast<f4 *>(x + (size_t)m * d + k + 4) = f4{v[4], v[5], v[6], v[7]};
-        const u4 pk = {f2a_pack(v[0] * g0[0], v[1] * g0[1]), f2a_pack(v[2] * g0[2], v[3] * g0[3]),
-                       f2a_pack(v[4] * g1[0], v[5] * g1[1]), f2a_pack(v[6] * g1[2], v[7] * g1[3])};
+        const u4 pk = {f2a_pack_f(v[0] * g0[0], v[1] * g0[1], flags), f2a_pack_f(v[2] * g0[2], v[3] * g0[3], flags),
+                       f2a_pack_f(v[4] * g1[0], v[5] * g1[1], flags), f2a_pack_f(v[6] * g1[2], v[7] * g1[3], flags)};
         *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
 #pragma unroll
         for (int q = 0; q < 8; ++q) sq += v[q] * v[q];
@@ -207,6 +207,7 @@ __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t
     Act<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
     Act<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
     const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
+    if ((unsigned)page >= (unsigned)n_pages) { atomicOr(flags, FLAG_BAD_PAGE); return; }      // bad table entry: the row's K/V are not written
     const int tok = slot & 15;
     const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
     Act<BF>::st(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn);
@@ -362,10 +363,11 @@ int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int par
 template <bool BF, bool WRITE>
 __global__ void kv_plain_kernel(typename Act<BF>::type *kpages, typename Act<BF>::type *vpages,
                                 const int32_t *page_table, int max_pages, int n_pages, int layer, int first_slot,
-                                int n_slots, int H, int Dh, float *plain) {
+                                int n_slots, int H, int Dh, float *plain, int32_t *flags) {
     const int b = blockIdx.z, i = blockIdx.x, h = blockIdx.y;
     const int slot = first_slot + i;
     const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
+    if ((unsigned)page >= (unsigned)n_pages) { if (threadIdx.x == 0) atomicOr(flags, FLAG_BAD_PAGE); return; }
     const int tok = slot & 15;
     const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
     float *pk = plain + ((((size_t)b * n_slots + i) * 2 + 0) * H + h) * Dh;
@@ -387,7 +389,7 @@ int launch_kv_plain(hydra_ctx *c, hipStream_t s, int B, int layer, const hydra_k
     const int H = c->m.n_heads, Dh = c->m.head_dim;
 #define KVP(BFv, Wv, TY)                                                                                             \
     hipLaunchKernelGGL((kv_plain_kernel<BFv, Wv>), grid, block, 0, s, (TY *)kv->k_pages, (TY *)kv->v_pages,           \
-                       kv->page_table, kv->max_pages, kv->n_pages, layer, first_slot, n_slots, H, Dh, plain)
+                       kv->page_table, kv->max_pages, kv->n_pages, layer, first_slot, n_slots, H, Dh, plain, flags_dev(c))
     if (c->bf16) { if (write_cache) KVP(true, true, a16_t); else KVP(true, false, a16_t); }
     else         { if (write_cache) KVP(false, true, float); else KVP(false, false, float); }
 #undef KVP
@@ -432,8 +434,8 @@ __global__ __launch_bounds__(256) void gather_prep_kernel(const float *__restric
             const f4 g0 = *reinterpret_cast<const f4 *>(gain + k), g1 = *reinterpret_cast<const f4 *>(gain + k + 4);
             *reinterpret_cast<f4 *>(x + (size_t)m * d + k) = v0;
             *reinterpret_cast<f4 *>(x + (size_t)m * d + k + 4) = v1;
-            const u4 pk = {f2a_pack(v0[0] * g0[0], v0[1] * g0[1]), f2a_pack(v0[2] * g0[2], v0[3] * g0[3]),
-                           f2a_pack(v1[0] * g1[0], v1[1] * g1[1]), f2a_pack(v1[2] * g1[2], v1[3] * g1[3])};
+            const u4 pk = {f2a_pack_f(v0[0] * g0[0], v0[1] * g0[1], flags), f2a_pack_f(v0[2] * g0[2], v0[3] * g0[3], flags),
+                           f2a_pack_f(v1[0] * g1[0], v1[1] * g1[1], flags), f2a_pack_f(v1[2] * g1[2], v1[3] * g1[3], flags)};
             *reinterpret_cast<u4 *>(xg + x_index<true>(m, k, d)) = pk;
             sq += v0[0] * v0[0] + v0[1] * v0[1] + v0[2] * v0[2] + v0[3] * v0[3] + v1[0] * v1[0] + v1[1] * v1[1] + v1[2] * v1[2] + v1[3] * v1[3];
         }

@@ -189,6 +189,9 @@ int launch_compact(hydra_ctx *c, hipStream_t s, int B, const int32_t *n_acc, con
 inline const TreeDev *tree_dev(const hydra_ctx *c) {
     return reinterpret_cast<const TreeDev *>(c->arena + c->off_tables + (size_t)c->table_slot * TABLE_SLOT_BYTES);
 }
+inline int32_t *flags_dev(const hydra_ctx *c) {
+    return reinterpret_cast<int32_t *>(c->arena + c->off_tables + (size_t)c->table_slot * TABLE_SLOT_BYTES + FLAGS_OFF_IN_SLOT);
+}
 inline const float *rope_dev(const hydra_ctx *c) { return reinterpret_cast<const float *>(c->arena + c->off_rope); }
 
 }  // namespace hydra
