@@ -96,6 +96,51 @@ def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu):
     return t_step, t_draft + t_head + t_verify_s
 
 
+SWEEP_T = (1, 2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128)
+SWEEP_B = (1, 2, 4, 8, 16)
+
+
+def tree_sweep(cfg, L0, steps, dev):
+    """Tree-size sweep (paper, section 4 "Discovering performant decoding trees" and the appendix on optimal trees):
+    proposal trees T_1 .. T_128 grown greedily under a synthetic acceptance model, one whole step (draft, verify,
+    accept, compact) timed for a ladder of sizes and batch sizes, and per batch size the size with the highest
+    expected tokens/s = B * E[acceptance length](T) / step time.  The expectation is a property of the synthetic
+    prior (synth/trees.py), not of a corpus; the step times are measured."""
+    from synth import WeightSpec, expected_acceptance, make_tensor, proposal_trees
+    from paper_2402_05109_amd.session import Session
+    trees = proposal_trees(max(SWEEP_T))
+    exp = {T: float(expected_acceptance(trees[T - 1])) for T in SWEEP_T}
+    spec = WeightSpec(cfg)
+    rows = []
+    for B in SWEEP_B:
+        sess = Session(cfg, trees[SWEEP_T[0] - 1], B, L0 + max(SWEEP_T) + 64, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=64)
+        names = {SWEEP_T[0]: "main"}
+        for T in SWEEP_T[1:]:
+            names[T] = f"tree{T}"
+            sess.add_tree(names[T], trees[T - 1])
+        per_T = []
+        for T in SWEEP_T:
+            nm = names[T]
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ts = []
+            for i in range(3 + steps):
+                sess.seq_len.fill_(L0); sess.host_len = L0              # cache content is irrelevant to the time of a step
+                ev0.record(); sess.step(nm); ev1.record(); ev1.synchronize()
+                if i >= 3:
+                    ts.append(ev0.elapsed_time(ev1))
+            ms = float(np.median(ts))
+            per_T.append({"T": T, "ms_per_step": ms, "expected_acceptance": exp[T], "tokens_per_s_expected": B * exp[T] / (ms * 1e-3)})
+        assert sess.main.read_flags() == 0
+        best = max(per_T, key=lambda r: r["tokens_per_s_expected"])
+        rows.append({"B": B, "best_T": best["T"], "tokens_per_s_expected": best["tokens_per_s_expected"],
+                     "ms_per_step_at_best": best["ms_per_step"], "autoregressive_tokens_per_s": per_T[0]["tokens_per_s_expected"], "per_T": per_T})
+        stage(f"tree sweep, batch {B}: best T = {best['T']}")
+        del sess
+        torch.cuda.empty_cache()
+    return {"prior": "synthetic acceptance model q(depth j, rank r) = 0.3 * 0.8^(j-1) * 0.5^r, not corpus statistics",
+            "context": L0, "sizes": list(SWEEP_T), "rows": rows}
+
+
 def stage(msg):
     """one progress line per finished stage, on stderr (stdout carries only the JSON line)"""
     print(f"bench.py: {msg}", file=sys.stderr, flush=True)
@@ -115,6 +160,8 @@ def main():
                     help="Medusa-style draft heads (h_last only, one hidden layer with a skip connection) instead of Hydra heads: the baseline draft cost")
     ap.add_argument("--typical", action="store_true",
                     help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
+    ap.add_argument("--sweep", action="store_true",
+                    help="only the tree-size sweep: step time for proposal trees of 1..128 nodes at batch 1..16 and the size of highest expected tokens/s per batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-injected", action="store_true",
                     help="skip the injected-acceptance points (for counter-collection runs, where every launch is slow)")
@@ -134,6 +181,13 @@ def main():
     cfg = CONFIGS[args.config]
     if args.layers:
         cfg = cfg.with_(NL=args.layers)
+    if args.sweep:
+        sw = tree_sweep(cfg, args.prompt or cfg.prompt[0], 8, "cuda:0")
+        print(json.dumps({"metric": "tree-size sweep: expected tokens/s per (T, B)", "unit": "tokens/s", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": f"config {args.config}: {cfg.name} shape, {cfg.K} heads x {cfg.mlp_layers}-layer MLP, proposal trees of "
+                                                 f"{SWEEP_T[0]}..{SWEEP_T[-1]} nodes, B in {list(SWEEP_B)}, context {args.prompt or cfg.prompt[0]}"},
+                          "tree_sweep": sw}))
+        return
     if args.tree:
         cfg = cfg.with_(T=args.tree)
     if args.medusa:

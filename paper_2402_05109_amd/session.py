@@ -132,6 +132,19 @@ class Session:
                 self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
         return self._ctx[name]
 
+    def add_tree(self, name: str, parent: Sequence[int]) -> hb.Hydra:
+        """A further decode context with its own candidate tree on the same weights and cache (the weight arena has
+        room for 16 contexts in all)."""
+        if name in self._ctx:
+            raise ValueError(f"context {name!r} exists")
+        c = self._make_ctx(name, list(parent))
+        self._bind(c)
+        need = c.workspace_bytes(self.B)
+        if need > self.ws.numel():
+            torch.cuda.synchronize()
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        return c
+
     # ---- prefix-attention contexts (one per chain length) --------------------------
     def _prefix_ctx_new(self, P: int) -> hb.Hydra:
         s = self.shape

@@ -81,6 +81,58 @@ def build_prior_tree(T: int, rank_caps) -> list:
     return tree_from_paths(have)
 
 
+# ---- proposal trees of every size and their expected acceptance length (tree-size sweep) ----------------
+# The tree-discovery section of the paper grows a sequence of proposal trees T_1, T_2, ..., each by adding the node
+# with the highest expected contribution to the acceptance length, estimated on a corpus, and then measures which
+# size gives the highest throughput.  There is no corpus here; the sweep uses a synthetic acceptance model that is a
+# proper probability model, so that "expected acceptance length" has a meaning:
+#   given that the path above it is accepted, the rank-r candidate of the head at depth j is the base model's next
+#   token with probability  q(j, r) = 0.3 * 0.8^(j-1) * 0.5^r        (sum over r below 1 at every depth).
+# Siblings are distinct tokens, so at most one child of a node is accepted, and
+#   P(node accepted) = product of q over the edges of its root path,
+#   E[acceptance length] = sum over all nodes of P(node accepted)   (the root counts 1).
+# Greedy growth by P(node accepted) therefore yields, for every size, a tree of maximal expected acceptance length,
+# and the trees are nested.  Numbers derived from it are properties of this synthetic prior, not corpus statistics.
+
+def accept_prob(path) -> Fraction:
+    """P(the node with this child-rank path lies on the accepted path) under the synthetic acceptance model."""
+    w = Fraction(1)
+    for j, r in enumerate(path):
+        w *= Fraction(3, 10) * Fraction(8, 10) ** j * Fraction(1, 2) ** r
+    return w
+
+
+def expected_acceptance(parent) -> Fraction:
+    """Expected number of tokens a step accepts with this tree under the synthetic acceptance model (root included)."""
+    return sum((accept_prob(p) for p in paths_from_parent(parent)), Fraction(0))
+
+
+def proposal_trees(N: int, rank_caps=(10, 10, 10, 10)) -> list:
+    """[T_1, ..., T_N] as parent lists: T_n has n nodes and adds to T_{n-1} the absent node of highest acceptance
+    probability whose parent and previous sibling are present (ties: shallower, then lexicographic)."""
+    have = {()}
+    out = [tree_from_paths(have)]
+    while len(have) < N:
+        best = None
+        for p in have:
+            if len(p) >= len(rank_caps):
+                continue
+            r = 0
+            while p + (r,) in have:
+                r += 1
+            if r >= rank_caps[len(p)]:
+                continue
+            cand = p + (r,)
+            key = (-accept_prob(cand), len(cand), cand)
+            if best is None or key < best[0]:
+                best = (key, cand)
+        if best is None:
+            raise ValueError("rank caps too small for the requested tree size")
+        have.add(best[1])
+        out.append(tree_from_paths(have))
+    return out
+
+
 def chain_tree(T: int) -> list:
     return [-1] + list(range(T - 1))
 

@@ -12,7 +12,7 @@ import pytest
 import torch
 
 from oracle import hydra_oracle as O
-from synth import chain_tree, frozen_tree, random_tree, star_tree, uniform_tokens
+from synth import chain_tree, frozen_tree, proposal_trees, random_tree, star_tree, uniform_tokens
 from helpers import make_weights, oracle_model, small_shape
 from gpu_util import VerifyAudit, gpu_session, load_oracle_cache, max_rel, near_tie, read_cache, to_np
 
@@ -37,7 +37,9 @@ def cache_round(a):
 
 TREES = {"tiny16": lambda: frozen_tree("tiny16"), "prior64": lambda: frozen_tree("prior64"),
          "prior128": lambda: frozen_tree("prior128"), "prior32": lambda: frozen_tree("prior32"),
-         "single": lambda: [-1], "chain40": lambda: chain_tree(40), "random70": lambda: random_tree(70, 4, 3)}
+         "single": lambda: [-1], "chain40": lambda: chain_tree(40), "random70": lambda: random_tree(70, 4, 3),
+         # proposal trees of the tree-size sweep (sizes that are none of the frozen workload trees)
+         "sweep12": lambda: proposal_trees(12)[-1], "sweep24": lambda: proposal_trees(24)[-1], "sweep48": lambda: proposal_trees(48)[-1]}
 
 
 @pytest.mark.parametrize("tree_name,L,B,Dh", [("prior64", 0, 1, 128), ("prior64", 1, 2, 128), ("prior64", 31, 1, 128),
@@ -153,6 +155,7 @@ def _audit_children(logits, kids, tol_abs):
 
 
 @pytest.mark.parametrize("tree_name,B,mlp", [("prior64", 1, 1), ("prior64", 2, 4), ("tiny16", 5, 2), ("prior128", 1, 1), ("single", 1, 1),
+                                             ("sweep12", 2, 1), ("sweep24", 1, 4), ("sweep48", 3, 1),
                                              ("prior64", 16, 2)])                          # 336 draft rows in the widest phase
 def test_draft_tree_matches_oracle(tree_name, B, mlp):
     print("case", tree_name, B, mlp, flush=True)
@@ -186,6 +189,7 @@ def test_draft_tree_matches_oracle(tree_name, B, mlp):
 
 @pytest.mark.parametrize("tree_name,B,L", [("prior64", 1, 37), ("prior64", 2, 64), ("tiny16", 3, 5), ("single", 2, 90),
                                             ("prior128", 1, 130), ("chain40", 1, 0), ("random70", 2, 33),
+                                            ("sweep12", 3, 50), ("sweep24", 2, 7), ("sweep48", 1, 100),
                                             ("prior64", 16, 21), ("prior128", 3, 9)])      # 1024 and 384 rows: several row groups per GEMM
 def test_tree_verify_forward_teacher_forced(tree_name, B, L):
     _verify_forward_teacher_forced(tree_name, B, L)

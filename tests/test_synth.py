@@ -90,3 +90,68 @@ def test_helper_trees_are_bfs_ordered():
             depth[n] = depth[parent[n]] + 1
             assert depth[n] >= depth[n - 1]                 # BFS: depth never decreases
             assert parent[n] >= parent[n - 1]               # children of a node are contiguous
+
+
+# ---- proposal trees of the tree-size sweep and their expected acceptance length ---------------------------------
+def _brute_force_expected_acceptance(parent, caps):
+    """Enumerates every outcome of the synthetic acceptance model: at depth j the base model's token is the rank-r
+    candidate with probability q(j, r), or none of the ranks with the rest; the step accepts the longest prefix of
+    the outcome's rank path that is a node of the tree.  Written from the model's statement, not from the sum over
+    nodes that expected_acceptance uses."""
+    from fractions import Fraction
+    from itertools import product
+    from synth import paths_from_parent
+    nodes = set(paths_from_parent(parent))
+    q = lambda j, r: Fraction(3, 10) * Fraction(8, 10) ** j * Fraction(1, 2) ** r
+    total, mass = Fraction(0), Fraction(0)
+    choices = [list(range(c)) + [None] for c in caps]
+    for outcome in product(*choices):
+        p = Fraction(1)
+        for j, r in enumerate(outcome):
+            p *= q(j, r) if r is not None else 1 - sum(q(j, rr) for rr in range(caps[j]))
+        mass += p
+        length, path = 1, ()
+        for r in outcome:
+            if r is None or path + (r,) not in nodes:
+                break
+            path += (r,)
+            length += 1
+        total += p * length
+    assert mass == 1
+    return total
+
+
+def test_expected_acceptance_equals_enumeration_of_all_outcomes():
+    from synth import expected_acceptance, proposal_trees, tree_from_paths
+    caps = (3, 3, 2)
+    for parent in proposal_trees(12, caps) + [tree_from_paths([(), (0,), (1,), (0, 0), (0, 1), (1, 0), (0, 0, 0), (0, 0, 1), (1, 0, 0)])]:
+        assert expected_acceptance(parent) == _brute_force_expected_acceptance(parent, caps)
+    assert expected_acceptance([-1]) == 1
+
+
+def test_proposal_trees_are_nested_valid_and_greedy():
+    from fractions import Fraction
+    from synth import accept_prob, expected_acceptance, paths_from_parent, proposal_trees
+    trees = proposal_trees(128)
+    assert [len(t) for t in trees] == list(range(1, 129))
+    prev_paths, prev_e = set(), Fraction(0)
+    for t in trees:
+        paths = paths_from_parent(t)
+        assert paths == sorted(paths, key=lambda p: (len(p), p))              # breadth-first order
+        assert all(t[n] < n for n in range(1, len(t))) and max(len(p) for p in paths) <= 4
+        s = set(paths)
+        assert prev_paths < s or not prev_paths                               # nested: one node more each time
+        added = s - prev_paths
+        if prev_paths:
+            (new,) = added
+            # greedy: no absent node whose parent and previous sibling are present is more probable than the one added
+            for p in prev_paths:
+                r = 0
+                while p + (r,) in prev_paths:
+                    r += 1
+                if len(p) < 4 and r < 10:
+                    assert accept_prob(p + (r,)) <= accept_prob(new)
+        e = expected_acceptance(t)
+        assert e > prev_e
+        prev_paths, prev_e = s, e
+    assert 1 < float(expected_acceptance(trees[63])) < 2                      # a modest prior: about 1.8 tokens per step at 64 nodes
