@@ -248,9 +248,32 @@ def main():
     t_tail = timed(lambda: (sess.accept(), sess.compact()))
     t_prefix = timed(sess.prefix_attention) if sess.prefix else None
     t_typical = None
+    typical_loop = None
     if args.typical:
         u_dev = torch.rand(B, device=dev)
         t_typical = timed(lambda: sess.accept_typical(0.7, 0.15, 0.15 ** 0.5, u_dev))
+        # the whole loop under the typical criterion (section 6.3's setting: tau 0.7, eps 0.15, alpha sqrt(eps)): draft ->
+        # verify (keeps the [B,T,V] logits) -> accept_typical with a fresh uniform number per row -> compact
+        saved = snapshot()
+        n_typ = 32
+        us = torch.rand(n_typ, B, device=dev)
+        acc_t = torch.zeros(n_typ, B, dtype=torch.int32, device=dev)
+        sess.step(typical=(0.7, 0.15, 0.15 ** 0.5, us[0]))
+        restore(saved)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_typ):
+            sess.step(typical=(0.7, 0.15, 0.15 ** 0.5, us[i]))
+            acc_t[i].copy_(o.n_acc)
+        torch.cuda.synchronize()
+        dt_t = time.perf_counter() - t0
+        tok_t = int(acc_t.sum().item())
+        typical_loop = {"steps": n_typ, "ms_per_step": dt_t / n_typ * 1e3, "tokens_per_s": tok_t / dt_t, "mean_acceptance": tok_t / (n_typ * B),
+                        "tau": 0.7, "eps": 0.15, "alpha": 0.15 ** 0.5,
+                        "note": "with random-init weights the logits are nearly flat, so nearly every candidate passes this criterion: the acceptance "
+                                "length is an artefact of the synthetic weights; the step time is real"}
+        restore(saved)
+        sess.sync_len()
     vb = verify_bytes(cfg, B, L_end, cfg.T)
 
     # dominant kernel: the weight-streaming GEMM.  HIP events (recorded by the library on the launch stream)
@@ -324,6 +347,7 @@ def main():
         "accept_compact_ms": t_tail,
         "prefix_attention_ms": t_prefix,
         "accept_typical_ms": t_typical,
+        "typical_acceptance_loop": typical_loop,
         "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
         "injected_acceptance": injected,
         "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",

@@ -517,20 +517,28 @@ def prefix_chunk(model, pcache, L, X):
     return Y + (silu(N2 @ m.w("prefix.w_gate").T) * (N2 @ m.w("prefix.w_up").T)) @ m.w("prefix.w_down").T
 
 
-def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None, pcache=None):
+def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None, pcache=None, typical=None):
     """One full step.  Returns (emitted tokens, new L, new h_last, new root, info).
 
     With `pcache` (Hydra++ prefix attention) h_last is the prefix layer's output at the
     last verified token: after acceptance the layer is fed the base hidden states of the
-    accepted tokens, one position each, and its last output becomes the new h_last."""
+    accepted tokens, one position each, and its last output becomes the new h_last.
+
+    typical = None: greedy acceptance (section 2).  typical = (tau, eps, alpha, u): the typical
+    acceptance criterion of section 6.3 decides the accepted path and the next root is the most
+    likely token at its end (u None) or drawn there at the uniform number u (see accept_typical)."""
     tok, _ = draft_tree(model, tree, h_last, root)
     if draft_hook is not None:
         tok = draft_hook(tok)
     hidden, logits, amax = tree_verify(model, cache, L, tree, tok)
-    n_acc, path, next_root, last = accept_greedy(tree, tok, amax)
+    if typical is None:
+        n_acc, path, next_root, last = accept_greedy(tree, tok, amax)
+    else:
+        tau, eps, alpha, u = typical
+        n_acc, path, next_root, last = accept_typical(tree, tok, logits, tau, eps, alpha, u)
     emitted = [int(tok[n]) for n in path]
     L2 = kv_compact(cache, L, path)
-    info = {"tok": tok, "argmax": amax, "path": path, "n_acc": n_acc, "logits": logits, "hidden": hidden}
+    info = {"tok": tok, "argmax": amax, "path": path, "n_acc": n_acc, "logits": logits, "hidden": hidden, "next_root": next_root}
     h_new = hidden[last]
     if pcache is not None:
         for j, n in enumerate(path):
@@ -538,9 +546,12 @@ def hydra_step(model, cache, tree, L, h_last, root, draft_hook=None, pcache=None
     return emitted, L2, h_new, next_root, info
 
 
-def hydra_generate(model, tree, prompt, n_new, draft_hook=None, capacity=None, prefix=False):
-    """Hydra decoding with greedy acceptance: the first n_new generated tokens
-    and the per-step acceptance lengths.  prefix=True: Hydra++ prefix attention."""
+def hydra_generate(model, tree, prompt, n_new, draft_hook=None, capacity=None, prefix=False, typical=None, u_per_step=None,
+                   step_log=None):
+    """Hydra decoding: the first n_new generated tokens and the per-step acceptance lengths.
+    Greedy acceptance unless typical = (tau, eps, alpha) is given (section 6.3); then step s draws its
+    next root at u_per_step[s] (u_per_step None: the most likely token).  prefix=True: Hydra++ prefix
+    attention.  step_log, if a list, receives every step's info dictionary."""
     cap = capacity or (len(prompt) + n_new + tree.T + tree.max_depth + 2)
     cache = FlatCache(model, cap)
     pcache = PrefixCache(model, cap) if prefix else None
@@ -555,7 +566,12 @@ def hydra_generate(model, tree, prompt, n_new, draft_hook=None, capacity=None, p
     out, acc = [], []
     while len(out) < n_new:
         hook = (lambda t, _n=len(out): draft_hook(t, _n)) if draft_hook else None
-        emitted, L, h_last, root, info = hydra_step(model, cache, tree, L, h_last, root, hook, pcache)
+        typ = None
+        if typical is not None:
+            typ = (typical[0], typical[1], typical[2], None if u_per_step is None else float(u_per_step[len(acc)]))
+        emitted, L, h_last, root, info = hydra_step(model, cache, tree, L, h_last, root, hook, pcache, typ)
         out += emitted
         acc.append(info["n_acc"])
+        if step_log is not None:
+            step_log.append(info)
     return out[:n_new], acc

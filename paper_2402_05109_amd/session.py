@@ -263,15 +263,19 @@ class Session:
         self.host_len += c.depth + 1          # upper bound; the device holds the exact value
         self._growth_since_copy += c.depth + 1
 
-    def step(self, name: str = "main", hook=None) -> None:
+    def step(self, name: str = "main", hook=None, typical=None) -> None:
         """One speculative step of every row.  `hook(outputs)` may edit tree_tokens between
-        draft and verify (scripted-acceptance experiments)."""
+        draft and verify (scripted-acceptance experiments).  typical = (tau, eps, alpha, u): the accepted path
+        and the next root come from accept_typical (u: device [B] uniform numbers or None) instead of accept_greedy."""
         self._refresh_bound()
         self.draft(name)
         if hook is not None:
             hook(self._out[name])
         self.verify(name)
-        self.accept(name)
+        if typical is None:
+            self.accept(name)
+        else:
+            self.accept_typical(typical[0], typical[1], typical[2], typical[3], name)
         pre = self.host_len
         self.compact(name)
         if self.prefix:

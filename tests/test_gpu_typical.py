@@ -112,3 +112,100 @@ def test_accept_typical_argument_checks():
         with pytest.raises(hb.HydraError) as e:
             sess.main.accept_typical(1, sess.ws, o.tree_tokens, o.logits, bad[0], bad[1], bad[2], None, o.n_acc, o.path, o.next_root, o.last_node)
         assert e.value.code == hb.E_INVALID_ARG
+
+
+def _near_threshold_or_cdf_step(tree, tok, logits, tau, eps, alpha, u, last):
+    """True if float32 could decide this step differently from float64: some candidate's probability within 1e-4
+    (relative) of its threshold, or u within 1e-5 of a step of the cumulative distribution at the last node."""
+    for c in range(1, tree.T):
+        p = O.tempered_probs(logits[tree.parent[c]], tau)
+        th = min(eps, alpha * np.exp(-O.entropy(p)))
+        if abs(p[tok[c]] - th) <= 1e-4 * th:
+            return True
+    cdf = np.cumsum(O.tempered_probs(logits[last], tau))
+    return bool(np.min(np.abs(cdf - u)) <= 1e-5)
+
+
+@pytest.mark.parametrize("prefix", [0, 1])
+def test_typical_acceptance_loop_matches_the_oracle_token_for_token(prefix):
+    """Section 6.3 as the criterion of the whole loop, fp32 tiny configuration, free running: draft -> verify ->
+    accept_typical (next root drawn at supplied uniform numbers) -> kv_compact (-> prefix layer), 32 tokens, against
+    the oracle's loop with the same numbers: emitted tokens, acceptance lengths and drawn roots, step by step, until
+    the first step whose decision float32 could take differently (counted; none is expected at this size)."""
+    from synth import CONFIGS, uniform_tokens
+    from helpers import oracle_model
+    cfg = CONFIGS[1].with_(prefix=prefix)
+    W = make_weights(cfg, gain_std=0.0)
+    m = oracle_model(cfg, W)
+    parent = frozen_tree("tiny16")
+    tree = O.Tree(parent)
+    prompt = uniform_tokens(cfg.seed, 0, 48, cfg.V)
+    # random-init logits are nearly flat (p about 1/V, exp(-H) about 1/V): with alpha = 1 a candidate passes iff its
+    # logit is above a tempered average, about every second one, so paths of all lengths occur
+    tau, eps, alpha = 1.0, 0.5, 1.0
+    us = np.random.default_rng(12).random(64).astype(np.float32)
+    log = []
+    want, want_acc = O.hydra_generate(m, tree, prompt.tolist(), 32, prefix=bool(prefix), typical=(tau, eps, alpha),
+                                      u_per_step=us.astype(np.float64), step_log=log)
+    sess = gpu_session(cfg, parent, 1, 48 + 32 + 24, W, prefill_chunk=16, want_logits=True)
+    sess.prefill(prompt.reshape(1, -1))
+    o = sess.out()
+    emitted, compared = [], 0
+    for s, info in enumerate(log):
+        ud = torch.tensor(us[s:s + 1], device="cuda:0")
+        sess.step(typical=(tau, eps, alpha, ud))
+        torch.cuda.synchronize()
+        assert sess.main.read_flags() == 0
+        na = int(o.n_acc[0])
+        got_path = o.path[0, :na].tolist()
+        risky = _near_threshold_or_cdf_step(tree, info["tok"], info["logits"], tau, eps, alpha, float(us[s]), info["path"][-1])
+        same = (o.tree_tokens[0].tolist() == info["tok"] and got_path == info["path"] and int(o.next_root[0]) == info["next_root"])
+        if not same:
+            assert risky, f"step {s}: the library and the oracle differ away from a threshold"
+            break
+        emitted += [info["tok"][n] for n in got_path]
+        compared += 1
+        sess.sync_len()
+    print(f"typical loop (prefix={prefix}): {compared} of {len(log)} steps compared, acceptance lengths {want_acc[:compared]}", flush=True)
+    assert compared >= len(log) - 1 and len(set(want_acc[:compared])) >= 3
+    assert emitted[:32] == want[:len(emitted[:32])]
+
+
+def test_typical_acceptance_step_in_the_16_bit_family_teacher_forced():
+    """One step of the 16-bit family with the library's own logits: accept_typical's integers must equal the oracle's
+    criterion evaluated on those very logits (rows near a threshold excluded and counted), and kv_compact must then
+    advance the state along that path."""
+    from test_gpu_bf16 import bf16_shape
+    cfg = bf16_shape()
+    W = make_weights(cfg, gain_std=0.1, std=0.05)
+    parent = frozen_tree("prior64")
+    tree = O.Tree(parent)
+    B, T, L = 3, tree.T, 40
+    sess = gpu_session(cfg, parent, B, 128, W, want_logits=True, page_perm_seed=4)
+    rng = np.random.default_rng(5)
+    for l in range(cfg.NL):
+        t = torch.tensor(rng.standard_normal((B, L, 2, cfg.H, cfg.Dh)) * 0.5, dtype=torch.float32, device="cuda:0")
+        sess.main.kv_write(B, l, sess.kv, 0, L, t)
+    sess.seq_len.fill_(L); sess.host_len = L
+    o = sess.out()
+    from synth import uniform_tokens
+    o.tree_tokens.copy_(torch.stack([uniform_tokens(9, b, T, cfg.V) for b in range(B)]).to(torch.int32))
+    sess.verify()
+    tau, eps, alpha = 3.0, 0.5, 0.9
+    u = torch.tensor(rng.random(B).astype(np.float32), device="cuda:0")
+    sess.accept_typical(tau, eps, alpha, u)
+    sess.compact()
+    torch.cuda.synchronize()
+    assert sess.main.read_flags() == 0
+    tok = o.tree_tokens.cpu().numpy(); lg = o.logits.cpu().numpy().astype(np.float64)
+    compared = 0
+    for b in range(B):
+        n_acc, path, nxt, last = O.accept_typical(tree, tok[b], lg[b], tau, eps, alpha, float(u[b]))
+        if _near_threshold_or_cdf_step(tree, tok[b], lg[b], tau, eps, alpha, float(u[b]), last):
+            continue
+        compared += 1
+        assert int(o.n_acc[b]) == n_acc and o.path[b, :n_acc].tolist() == path and int(o.next_root[b]) == nxt
+        assert int(sess.seq_len[b]) == L + n_acc and int(sess.root[b]) == nxt
+        assert torch.equal(sess.h_last[b], o.hidden[b, last])
+    print("16-bit typical step: rows compared", compared, "lengths", o.n_acc.tolist(), flush=True)
+    assert compared >= B - 1 and int(o.n_acc.max()) >= 2

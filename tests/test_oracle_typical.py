@@ -123,3 +123,64 @@ def test_accept_typical_uses_the_tempered_distribution_of_the_last_node():
     p = sp_softmax(logits[1] / 0.5)
     assert nxt == int(np.searchsorted(np.cumsum(p), 0.49, side="right")) == 2
     assert O.accept_typical(tree, tok, logits, 0.5, 0.2, 0.4, u=0.51)[2] == 3
+
+
+# ---- typical acceptance as a decoding loop (section 6.3 as the verification criterion of the whole procedure) ----
+def _tiny_model(std=0.3, **kw):
+    from helpers import make_weights, oracle_model, small_shape
+    cfg = small_shape(**kw)
+    return cfg, oracle_model(cfg, make_weights(cfg, gain_std=0.2, std=std))
+
+
+def test_loop_with_small_temperature_reproduces_greedy_text():
+    """tau -> 0 makes p one-hot on the base model's most likely token: a candidate passes iff it is that token, and the
+    next root is that token, so the loop is Hydra decoding with greedy acceptance and its text is plain greedy text."""
+    from synth import uniform_tokens
+    cfg, m = _tiny_model()
+    tree = O.Tree(frozen_tree("tiny16"))
+    prompt = uniform_tokens(5, 0, 9, cfg.V).tolist()
+    truth = O.ar_generate(m, prompt, 14)
+    want, want_acc = O.hydra_generate(m, tree, prompt, 14)
+    got, acc = O.hydra_generate(m, tree, prompt, 14, typical=(1e-3, 0.3, 0.5))
+    assert got == truth == want and acc == want_acc
+
+
+def test_loop_emits_only_root_paths_whose_every_token_passes_and_no_deeper_one_exists():
+    """Every step of the loop: the emitted tokens are the tokens of a root path of the tree, each non-root token of it
+    passes the per-token test against its parent's logits, no complete passing path is deeper (brute force over all
+    root paths), the next root is the inverse of the cumulative distribution at the last node, and the next step's
+    root is that token.  A flat temperature makes many candidates pass, so paths of several lengths occur."""
+    from synth import uniform_tokens
+    cfg, m = _tiny_model()
+    tree = O.Tree(frozen_tree("tiny16"))
+    prompt = uniform_tokens(6, 0, 8, cfg.V).tolist()
+    tau, eps, alpha = 2.0, 0.5, 0.8
+    rng = np.random.default_rng(3)
+    us = rng.random(40)
+    log = []
+    out, acc = O.hydra_generate(m, tree, prompt, 24, typical=(tau, eps, alpha), u_per_step=us, step_log=log)
+    assert len(set(acc)) >= 3 and max(acc) >= 3
+    emitted = []
+    for s, info in enumerate(log):
+        tok, lg, path = info["tok"], info["logits"], info["path"]
+        assert path[0] == 0 and all(tree.parent[path[j]] == path[j - 1] for j in range(1, len(path)))
+        for j in range(1, len(path)):
+            assert O.typical_pass(lg[path[j - 1]], tok[path[j]], tau, eps, alpha)
+        deepest = 1
+        for n in range(tree.T):                                            # brute force over all root paths
+            pth = tree.path(n)
+            if all(O.typical_pass(lg[pth[j - 1]], tok[pth[j]], tau, eps, alpha) for j in range(1, len(pth))):
+                deepest = max(deepest, len(pth))
+        assert len(path) == deepest == acc[s]
+        p = O.tempered_probs(lg[path[-1]], tau)
+        c = np.cumsum(p)
+        v = info["next_root"]
+        assert c[v] > us[s] * c[-1] and (v == 0 or c[v - 1] <= us[s] * c[-1])
+        if s + 1 < len(log):
+            assert log[s + 1]["tok"][0] == v                                 # the drawn token is the next step's root
+        emitted += [int(tok[n]) for n in path]
+    assert emitted[:24] == out
+    # the same draws give the same text; other draws another one
+    again, _ = O.hydra_generate(m, tree, prompt, 24, typical=(tau, eps, alpha), u_per_step=us)
+    other, _ = O.hydra_generate(m, tree, prompt, 24, typical=(tau, eps, alpha), u_per_step=rng.random(40))
+    assert again == out and other != out
