@@ -49,20 +49,39 @@ def draft_bytes(cfg):
 
 
 def read_traffic(config):
-    """HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)."""
-    path = os.path.join(ROOT, "profiles", f"gemm_bf16_kernel_config{config}_traffic.txt")
+    """HBM bytes per GEMM launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), and where the
+    figure comes from: counters cannot be read inside this run, so the committed summary is quoted together with the
+    commit that last touched it (a summary older than the kernels it describes is visible that way)."""
+    name = f"gemm_bf16_kernel_config{config}_traffic.txt"
+    path = os.path.join(ROOT, "profiles", name)
     try:
+        val = None
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                val = float(line.split(":")[1])
+        if val is None:
+            return None, None
+        src = f"profiles/{name}"
+        try:
+            import subprocess
+            r = subprocess.run(["git", "-C", ROOT, "log", "-1", "--format=%h %cs", "--", f"profiles/{name}"], capture_output=True, text=True, timeout=10)
+            if r.returncode == 0 and r.stdout.strip():
+                src += f" (last changed in commit {r.stdout.strip()})"
+        except Exception:
+            pass
+        return val, src
     except OSError:
-        pass
-    return None
+        return None, None
 
 
-def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu):
+def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu, threads=None):
     """Oracle on the host cores: one Hydra step (draft + verify) of the same shape with
-    `n_layers_sample` of the NL decoder layers, layer time scaled to NL."""
+    `n_layers_sample` of the NL decoder layers, layer time scaled to NL.  threads: limit of the BLAS thread pool
+    (None = all it takes by itself)."""
+    if threads is not None:
+        import threadpoolctl
+        with threadpoolctl.threadpool_limits(limits=threads):
+            return cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu)
     from oracle import hydra_oracle as O
     tree = O.Tree(parent)
     names = ["embed", "lm_head", "final_norm"]
@@ -94,6 +113,59 @@ def cpu_baseline(cfg, parent, L, n_layers_sample, get_cpu):
     per_layer = max(t_verify_s - t_head, 0.0) / n_layers_sample
     t_step = t_draft + t_head + per_layer * cfg.NL
     return t_step, t_draft + t_head + t_verify_s
+
+
+MFMA_PEAK_TFLOPS = 2500.0          # dense 16-bit matrix-core peak of MI355X (the contractions run mfma_f32_32x32x16_f16)
+
+
+def verify_flops(cfg, B, T):
+    """Multiply-adds x 2 of the weight contractions of one tree_verify_forward over B * T rows."""
+    return 2.0 * B * T * (cfg.NL * (4 * cfg.d * cfg.d + 3 * cfg.d * cfg.F) + cfg.d * cfg.V)
+
+
+def rooflines(cfg, B, L, T, ms):
+    """Both rooflines of a verify step: HBM (algorithmic bytes over 8 TB/s) and matrix cores (flops over 2.5 PFLOP/s);
+    the one whose floor is higher bounds the step (paper, section 6.2: large batch x tree makes verification compute-bound)."""
+    vb, fl = verify_bytes(cfg, B, L, T), verify_flops(cfg, B, T)
+    hbm_floor, mfma_floor = vb / 8e12 * 1e3, fl / (MFMA_PEAK_TFLOPS * 1e12) * 1e3
+    return {"rows": B * T, "ms": ms, "algorithmic_GB": vb / 1e9, "GBps": vb / (ms * 1e-3) / 1e9, "frac_of_8TBps": vb / (ms * 1e-3) / 8e12,
+            "TFLOPs": fl / (ms * 1e-3) / 1e12, "frac_of_mfma_peak": fl / (ms * 1e-3) / (MFMA_PEAK_TFLOPS * 1e12),
+            "bound": "mfma" if mfma_floor > hbm_floor else "hbm", "floor_ms": max(hbm_floor, mfma_floor)}
+
+
+def other_configs(budget_s, dev, reps=20):
+    """Verify-step latency and roofline fractions of the other workload configurations (3: 7B shape with Hydra++
+    heads at batch 1..16 and prompt 1024; 4: 13B shape at contexts 512 / 2048 / 4096; 5: 33B shape at batch 1 and 4,
+    context 2048), each on a session of its own with seeded weights.  The cache content does not influence the time
+    of a step, so the context is set, not prefilled.  Stops opening new sessions once the time budget is used up."""
+    from synth import CONFIGS, WeightSpec, frozen_tree, make_tensor
+    from paper_2402_05109_amd.session import Session
+    plan = [(3, B, (1024,)) for B in (1, 4, 8, 16)] + [(4, 1, (512, 2048, 4096))] + [(5, 1, (2048,)), (5, 4, (2048,))]
+    t_start, rows, skipped = time.perf_counter(), [], []
+    for idx, B, contexts in plan:
+        if time.perf_counter() - t_start > budget_s:
+            skipped.append(f"config {idx} B={B}")
+            continue
+        cfg = CONFIGS[idx]
+        spec = WeightSpec(cfg)
+        parent = frozen_tree("prior64")
+        sess = Session(cfg, parent, B, max(contexts) + 2 * cfg.T, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=64)
+        for L in contexts:
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ts = []
+            for i in range(3 + reps):
+                sess.seq_len.fill_(L); sess.host_len = L
+                ev0.record(); sess.verify(); ev1.record(); ev1.synchronize()
+                if i >= 3:
+                    ts.append(ev0.elapsed_time(ev1))
+            r = rooflines(cfg, B, L, cfg.T, float(np.median(ts)))
+            r.update({"config": idx, "shape": cfg.name, "B": B, "T": cfg.T, "context": L, "device_flags": sess.main.read_flags()})
+            rows.append(r)
+        stage(f"config {idx} B={B} measured")
+        del sess
+        torch.cuda.empty_cache()
+    return {"what": "tree_verify_forward, median of %d calls (HIP events), seeded weights, context set not prefilled" % reps,
+            "rows": rows, "skipped_for_time": skipped}
 
 
 SWEEP_T = (1, 2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128)
@@ -163,6 +235,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="only the tree-size sweep: step time for proposal trees of 1..128 nodes at batch 1..16 and the size of highest expected tokens/s per batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-configs-budget", type=float, default=75.0,
+                    help="seconds the default run may spend on the verify-step figures of configs 3, 4 and 5 (0 = skip them)")
     ap.add_argument("--no-injected", action="store_true",
                     help="skip the injected-acceptance points (for counter-collection runs, where every launch is slow)")
     ap.add_argument("--layers", type=int, default=0, help="debug: override the number of layers (invalidates the result)")
@@ -233,7 +307,7 @@ def main():
         if sess.prefix:
             sess.pseq_len.copy_(saved[4])
 
-    def timed(fn, reps=20):
+    def timed(fn, reps=50):
         saved = snapshot()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ts = []
@@ -287,7 +361,7 @@ def main():
     stage("per-call timings done")
     peak = 8000.0
     ach = (w_bytes / n_launch) / (ms_sum / n_launch * 1e-3) / 1e9 if n_launch else 0.0
-    traffic = read_traffic(args.config)
+    traffic, traffic_src = read_traffic(args.config)
     # throughput at injected acceptance lengths: between verify and accept, the base model's greedy token at the
     # first j nodes of the left-most root-to-leaf path is overwritten with the drafted child token, so accept_greedy
     # returns a fixed length (the generated text is then meaningless; only the cost of the step is real)
@@ -351,13 +425,18 @@ def main():
         "autoregressive_same_kernels": {"ms_per_token": t_ar, "tokens_per_s": 1e3 / t_ar * B},
         "injected_acceptance": injected,
         "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel" if cfg.dtype == "bf16" else "gemm_f32_kernel",
-                     "achieved": ach, "peak": peak, "unit": "GB/s", "frac": ach / peak, "traffic": traffic,
+                     "achieved": ach, "peak": peak, "unit": "GB/s", "frac": ach / peak, "traffic": traffic, "traffic_source": traffic_src,
                      "launches_timed": n_launch, "avg_launch_us": ms_sum / max(n_launch, 1) * 1e3,
                      "algorithmic_bytes_per_launch": w_bytes / max(n_launch, 1),
                      "timing": "HIP events attached to each launch on its stream (they take the kernel's own begin and end times)",
                      "scope": "the 129 GEMM launches of one tree_verify_forward (4 per layer + LM head), averaged over 8 calls"},
     }
     stage("injected-acceptance points done")
+    out["verify"].update({k: v for k, v in rooflines(cfg, B, L_end, cfg.T, t_verify).items() if k in ("rows", "TFLOPs", "frac_of_mfma_peak", "bound", "floor_ms")})
+    if args.other_configs_budget > 0 and args.config == 2 and not args.layers:
+        del sess
+        torch.cuda.empty_cache()
+        out["other_configs"] = other_configs(args.other_configs_budget, dev)
     if not args.no_cpu_baseline:
         ns = min(8, cfg.NL)
         cores = os.cpu_count() or 1
@@ -373,6 +452,15 @@ def main():
                                "sample": f"one Hydra step (all {cfg.K} draft heads, LM head, T={cfg.T} tree, context {L0}) with "
                                          f"{ns} of {cfg.NL} decoder layers timed ({t_spent:.1f} s of CPU work) and the per-layer time "
                                          f"scaled to {cfg.NL} layers; acceptance 1 token/step"}
+        stage("oracle timed on all threads")
+        try:
+            ns1 = min(1, cfg.NL)
+            t_step1, t_spent1 = cpu_baseline(cfg, parent, L0, ns1, cpu, threads=1)
+            out["cpu_baseline"]["one_thread"] = {"value": B / t_step1, "unit": "tokens/s", "cores": 1,
+                                                 "sample": f"the same step with {ns1} of {cfg.NL} decoder layers timed on one thread ({t_spent1:.1f} s of CPU work), scaled the same way"}
+            stage("oracle timed on one thread")
+        except Exception as e:                     # no thread-pool control on this host: the all-threads figure stands alone
+            out["cpu_baseline"]["one_thread"] = {"value": None, "note": f"not measured: {e}"}
     print(json.dumps(out))
 
 
