@@ -40,8 +40,11 @@ __device__ __forceinline__ void load_kv_tile(KVTile<DH> &kv, const a16_t *kpages
 // bf16_attn.hip, lds its ATTN_WAVES * 64 + ATTN_WAVES * (DH / 32) * 1024 floats of shared memory.  DEV: the final
 // output is written with device-scope stores (the reader is another workgroup of the same kernel).  The function
 // contains two workgroup barriers that every wave reaches unless the row is over capacity (uniform early return).
-// tid: the thread's index in the workgroup.
-template <int DH, bool PACKED, bool DEV>
+// tid: the thread's index in the workgroup.  QLDS: the query tiles are kept in LDS instead of registers, which takes
+// 8 * DH / 32 registers per lane off a kernel that sits at the limit of 256.  They lie in the space of the O merge
+// buffers (QW * DH * 64 bytes, never more than those), which are first written behind the barrier that follows the
+// key loops of all waves.
+template <int DH, bool PACKED, bool DEV, bool QLDS>
 __device__ __forceinline__ void attn_bf16_body(
     const u32x4_t *__restrict__ qbuf, const a16_t *__restrict__ kpages, const a16_t *__restrict__ vpages,
     const int32_t *__restrict__ page_table, int max_pages, int n_pages, int layer, const int32_t *__restrict__ seq_len,
@@ -73,6 +76,11 @@ __device__ __forceinline__ void attn_bf16_body(
         const size_t blk = (((size_t)b * H + h) * QTtot + qtile) * KS;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qreg[s] = qbuf[(blk + s) * 64 + lane];
+        if (QLDS && kwv == 0) {                            // one copy per query tile, written by the first wave of its key split
+            u32x4_t *qs = reinterpret_cast<u32x4_t *>(lds + ATTN_WAVES * 64) + (size_t)qw * KS * 64;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) qs[s * 64 + lane] = qreg[s];
+        }
         const int query = qtile * 32 + col;
         if (query < T) { anc0 = tree->anc[query][0]; anc1 = tree->anc[query][1]; }
 #pragma unroll
@@ -83,6 +91,8 @@ __device__ __forceinline__ void attn_bf16_body(
         }
     }
     const int L = seq_len[b];
+    if (QLDS) __syncthreads();                             // the query tiles are in LDS (before any early return: every wave reaches it)
+    const u32x4_t *qlds = reinterpret_cast<const u32x4_t *>(lds + ATTN_WAVES * 64) + (size_t)qw * KS * 64 + lane;
     if (L < 0 || L + T > max_pages * 16) {                 // uniform over the workgroup
         if (tid == 0 && bx == 0 && h == 0) atomicOr(flags, FLAG_CAPACITY);
         return;
@@ -142,9 +152,11 @@ __device__ __forceinline__ void attn_bf16_body(
             f32x16_t sc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+            int qoff = 0;
+            if (QLDS) asm volatile("" : "+v"(qoff));           // keeps the LDS reads of the queries inside the loop (hoisted, they are registers again)
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                sc = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, cur.k[s]), __builtin_bit_cast(a16x8_t, qreg[s]), sc);
+                sc = HYDRA_MFMA16(__builtin_bit_cast(a16x8_t, cur.k[s]), __builtin_bit_cast(a16x8_t, QLDS ? qlds[qoff + s * 64] : qreg[s]), sc);
             const bool need_mask = slot0 + 32 > L;
             float cmax = -INFINITY;
 #pragma unroll

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void attn_bf16_kernel(
     const TreeDev *__restrict__ tree, int T, int H, int QW, int qsplit, float scale, float *__restrict__ apart, void *out,
     int32_t *flags) {
     extern __shared__ float lds[];
-    attn_bf16_body<DH, PACKED, false>(qbuf, kpages, vpages, page_table, max_pages, n_pages, layer, seq_len, tree, T, H, QW, qsplit,
+    attn_bf16_body<DH, PACKED, false, true>(qbuf, kpages, vpages, page_table, max_pages, n_pages, layer, seq_len, tree, T, H, QW, qsplit,
                                       scale, apart, out, flags, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y, (int)blockIdx.z, lds, (int)threadIdx.x);
 }
 

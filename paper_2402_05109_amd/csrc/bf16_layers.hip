@@ -421,7 +421,7 @@ template <int MB> struct LkShape {
     // k-steps per register set.  With two row blocks the accumulators, two weight sets and two activation sets of
     // four k-steps fill all 256 registers of a wave, and anything else that is live pushes weight tiles into scratch
     // memory (whose reloads wait for every older load: the end of the software pipeline); three k-steps leave room.
-    static constexpr int U_Q = MB == 2 ? 3 : 4, U_O = MB == 2 ? 3 : 4, U_G = 2, U_D = MB == 2 ? 3 : 4;
+    static constexpr int U_Q = 3, U_O = 3, U_G = 2, U_D = 3;
 };
 
 template <int MB, int DH>
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(LK_THREADS) void layers_kernel(LayerKernelArgs A) {
         if (attn_wg) {
             const int it = (int)blockIdx.x;
             const int qt = it % A.QT, h = (it / A.QT) % A.H, b = it / (A.QT * A.H);
-            attn_bf16_body<DH, true, true>(reinterpret_cast<const u32x4_t *>(qbuf), A.kpages, A.vpages, A.page_table, A.max_pages, A.n_pages, l,
+            attn_bf16_body<DH, true, true, false>(reinterpret_cast<const u32x4_t *>(qbuf), A.kpages, A.vpages, A.page_table, A.max_pages, A.n_pages, l,
                                            A.seq_len, A.tree, A.T, A.H, 1, 1, A.scale, nullptr, attn, A.flags, qt, A.QT, h, b, lds, opaque_tid());
             wg_barrier_lds();                           // the attention body's LDS is the next step's
         }
@@ -635,9 +635,9 @@ static LkPlan lk_plan(const hydra_ctx *c, int B) {
     const int groups_d = ceil_div(d / 32, 2);
     if (groups_d > G) return p;
     const int room = G - p.n_attn >= groups_d ? G - p.n_attn : G;
-    p.o = split_plan(groups_d, d / 16, room, p.MB == 2 ? 3 : 4);
+    p.o = split_plan(groups_d, d / 16, room, 3);
     p.o.off = (room == G) ? 0 : p.n_attn;
-    p.dn = split_plan(groups_d, F / 16, G, p.MB == 2 ? 3 : 4);
+    p.dn = split_plan(groups_d, F / 16, G, 3);
     if (p.o.n_items > G || p.dn.n_items > G) return p;
     // the gate/up items leave workgroups idle: start them where the O items end, so that other workgroups idle in the two steps
     p.gu.off = 0;
