@@ -137,7 +137,9 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
     g.M = M; g.NTiles = ceil_div(N, 32); g.KT = K / 16; g.kpw = p.kpw; g.NW = p.nw; g.KW = p.kw;
     const int groups = ceil_div(g.NTiles, p.nt);
     dim3 grid(ceil_div(groups, p.nw), p.splits, ceil_div(ceil_div(M, 32), p.mb)), block(p.nw * p.kw * 64);
-    if (Epi::EXTRA_BLOCKS && !p.shared_x && grid.y == 1 && grid.z == 1) grid.x += extra_blocks;    // see Epilogue::extra_block
+    g.gx = (int)grid.x; g.gy = (int)grid.y; g.gz = (int)grid.z;
+    if (grid.z > 1) grid = dim3((unsigned)(ceil_div(g.gx * g.gy, 8) * 8 * g.gz), 1, 1);          // see gemm_block()
+    if (Epi::EXTRA_BLOCKS && !p.shared_x && g.gy == 1 && g.gz == 1) grid.x += extra_blocks;      // see Epilogue::extra_block
     size_t lds = ((size_t)GEMM_LDS_SCRATCH + (p.kw > 1 ? (size_t)p.kw * p.nw * p.mb * p.nt * 16 * 64 : 0)) * 4;
     if (p.shared_x) {
         if (p.mb != 4 || p.nt != 2 || p.kw != 1 || p.splits != 1 || p.nw != p.shared_x || (p.shared_x != 4 && p.shared_x != 8))

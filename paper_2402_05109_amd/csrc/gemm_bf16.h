@@ -54,7 +54,22 @@ struct GemmGeom {
     int KT;         // k-steps of 16 in K
     int kpw;        // k-steps per wave
     int NW, KW;     // waves per workgroup along N and K (KW a power of two)
+    int gx, gy, gz; // gz > 1 (several row groups): the grid is one-dimensional and gemm_block() maps it onto (gx, gy, gz)
 };
+
+// Which (band group, K split, row group) a workgroup takes.  With several row groups the workgroups that stream the
+// same weight bands should meet in one L2: workgroups are handed to the 8 XCDs in turn, so workgroup i runs on XCD
+// i % 8, and the row groups of one (band group, split) take consecutive places on one XCD.  The grid is rounded up
+// to whole sets of 8 (band group, split) pairs; false: no such pair (the whole workgroup leaves).
+__device__ __forceinline__ bool gemm_block(const GemmGeom &g, int &bx, int &by, int &bz) {
+    if (g.gz <= 1) { bx = (int)blockIdx.x; by = (int)blockIdx.y; bz = 0; return true; }
+    const int i = (int)blockIdx.x, xcd = i & 7, j = i >> 3;
+    bz = j % g.gz;
+    const int q = (j / g.gz) * 8 + xcd;
+    bx = q % g.gx;
+    by = q / g.gx;
+    return q < g.gx * g.gy;
+}
 
 // floats reserved in front of the reduction buffer: per-wave partial row sums [8 waves][128 rows], then per
 // wave a 1 KiB staging block (epilogues that assemble whole operand tiles) and a 128-row table of row scales
@@ -123,7 +138,8 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
         for (int u = 0; u < GEMM_U; ++u) {
             const int k = min(k0 + u, g.KT - 1);         // clamped: a ragged tail re-reads a valid tile and skips its MFMA
 #pragma unroll
-            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // used once: streaming load
+            for (int i = 0; i < NT; ++i)            // a streaming load where each byte is used once; with four row blocks there may be
+                w[u][i] = MB == 4 ? wrow[i][(size_t)k * 64] : __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // other row groups: keep it in L2
 #pragma unroll
             for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
         }
@@ -140,12 +156,13 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
             }
         }
     };
-    // k-blocks of U steps are visited in an order rotated by the band-group index, so that the
-    // workgroups streaming different bands do not all ask the L2 for the same X lines at once.  The
-    // workgroups of different row groups that stream the same bands keep the same order: they sit on the
-    // same XCD (the grid's x extent is a multiple of 8 or they are few) and so share each W line in its L2.
+    // Few rows (X is small): k-blocks of U steps are visited in an order rotated by the band-group index, so that
+    // the workgroups streaming different bands do not all ask the L2 for the same X lines at once.  With four row
+    // blocks per workgroup X is large (M x K), and every band group re-reads it: there all workgroups walk K in the
+    // same order, so that the part of X in use at any time fits in L2 (rotated, each band group's X reads missed:
+    // 5-6 times the weight bytes were fetched from memory at 1024 rows).
     const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
-    const int rot = nblk > 0 ? (int)(((unsigned)bx * 5u) % (unsigned)nblk) : 0;
+    const int rot = (MB < 4 && nblk > 0) ? (int)(((unsigned)bx * 5u) % (unsigned)nblk) : 0;
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
     // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
     // unconditional: only then can the compiler count how many loads are younger than the set it is about to
@@ -259,9 +276,11 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
     if constexpr (Epilogue::EXTRA_BLOCKS) {        // workgroups behind the last band group: side work of the epilogue's choosing
         const int wgs = ((g.NTiles + NT - 1) / NT + g.NW - 1) / g.NW;
-        if ((int)blockIdx.x >= wgs) { epi.extra_block((int)blockIdx.x - wgs, (int)gridDim.x - wgs, g); return; }
+        if (g.gz <= 1 && (int)blockIdx.x >= wgs) { epi.extra_block((int)blockIdx.x - wgs, (int)gridDim.x - wgs, g); return; }
     }
-    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, red);
+    int bx, by, bz;
+    if (!gemm_block(g, bx, by, bz)) return;
+    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, bx, by, bz, red);
 }
 
 // Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
@@ -279,9 +298,11 @@ template <int MB, int NT, int NWT, class Epilogue, int GEMM_U = 4>
 __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g, Epilogue epi) {
     extern __shared__ float red[];                 // [scratch] + 2 x [GEMM_U][MB] X tiles of 1 KiB
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int bx, by, bz;
+    if (!gemm_block(g, bx, by, bz)) return;
     GemmTile<MB, NT> t;
-    t.tile0 = ((int)blockIdx.x * NWT + wave) * NT;
-    t.mb0 = blockIdx.z * MB;
+    t.tile0 = (bx * NWT + wave) * NT;
+    t.mb0 = bz * MB;
     t.lane = lane;
     t.wave = wave;
     t.split = 0;
@@ -303,15 +324,14 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
             for (int v = 0; v < 16; ++v) acc[a][i][v] = 0.f;
 
     const int nblk = (g.KT + GEMM_U - 1) / GEMM_U;
-    const int rot = (int)((blockIdx.x * 5u) % (unsigned)nblk);     // the same for all waves of the workgroup and for all row groups
-    auto kof = [&](int j) { if (j >= nblk) return g.KT - 1; int q = j + rot; if (q >= nblk) q -= nblk; return q * GEMM_U; };
+    auto kof = [&](int j) { return j >= nblk ? g.KT - 1 : j * GEMM_U; };      // every workgroup walks K in the same order: the part of X in use fits in L2
     u32x4_t wa[GEMM_U][NT], wb[GEMM_U][NT], xs[XS];
     auto load_w = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
 #pragma unroll
         for (int u = 0; u < GEMM_U; ++u) {
             const int k = min(k0 + u, g.KT - 1);
 #pragma unroll
-            for (int i = 0; i < NT; ++i) w[u][i] = __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);
+            for (int i = 0; i < NT; ++i) w[u][i] = wrow[i][(size_t)k * 64];      // not a streaming load: the other row groups on this XCD read the same lines
         }
     };
     // tile q of a block: k-step q / MB, row block q % MB; this wave fetches q = wave, wave + NWT, ...
