@@ -213,6 +213,76 @@ def tree_sweep(cfg, L0, steps, dev):
             "context": L0, "sizes": list(SWEEP_T), "rows": rows}
 
 
+def layer_kernel_timeline(cfg, L, dev, layers=8):
+    """Where the time goes inside the persistent layer kernel (HYDRA_LAYER_KERNEL=1): wall-clock stamps that every
+    workgroup leaves per step and layer, reduced to per-step figures (mean over the inner layers).  Also times the same
+    verify call with separate launches.  The model is cut to `layers` decoder layers (the stamps of all workgroups of
+    32 layers are not needed for a per-layer figure)."""
+    import numpy as np
+    from synth import WeightSpec, frozen_tree, make_tensor, uniform_tokens
+    from paper_2402_05109_amd.session import Session
+    cfg = cfg.with_(NL=layers, K=1)
+    spec = WeightSpec(cfg)
+    parent = frozen_tree({16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T])
+    T = len(parent)
+
+    def timed(env):
+        for k in ("HYDRA_LAYER_KERNEL", "HYDRA_LAYER_KERNEL_STAMPS"):
+            os.environ.pop(k, None)
+        os.environ.update(env)
+        sess = Session(cfg, parent, 1, L + 64, lambda n: make_tensor(spec, n, device=dev), device=dev, prefill_chunk=64)
+        sess.out().tree_tokens.copy_(uniform_tokens(99, 0, T, cfg.V).reshape(1, -1).to(torch.int32))
+        sess.seq_len.fill_(L)
+        sess.host_len = L
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(12):
+            sess.seq_len.fill_(L)
+            e0.record(); sess.verify(); e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return sess, sorted(ts[2:])[5]
+
+    _, ms_launches = timed({})
+    sess, ms_kernel = timed({"HYDRA_LAYER_KERNEL": "1", "HYDRA_LAYER_KERNEL_STAMPS": "1"})
+    info = sess.main.layer_kernel_info(1)          # eligible, byte offset of the stamps in the workspace, workgroups, steps
+    if not info[0]:
+        return {"error": "the layer kernel does not take this shape"}
+    G, NS = info[2], info[3]
+    st = sess.ws[info[1]:info[1] + layers * NS * G * 8 * 8].view(torch.int64).cpu().numpy().reshape(layers, NS, G, 8).astype(np.float64) * 0.01
+    flags = sess.main.read_flags()
+    names = ["q|k|v GEMM + RoPE + cache append", "tree attention", "O GEMM", "residual + norm 1", "gate/up GEMM + SwiGLU", "down GEMM", "residual + norm 2"]
+    steps, per_layer = [], 0.0
+    for s in range(NS):
+        rows = []
+        for l in range(1, layers - 1):
+            b, e, a, r = st[l, s, :, 0], st[l, s, :, 1], st[l, s, :, 2], st[l, s, :, 3]      # begin, work done, counted in, released
+            work = e - b
+            gemm = s in (0, 2, 4, 5)
+            q = st[l, s]
+            if gemm:    # GEMM steps also stamp: first X tile in, last MFMA, stores issued (only workgroups with an item write them)
+                busy = (q[:, 4] >= b) & (q[:, 5] >= q[:, 4]) & (q[:, 6] >= q[:, 5]) & (q[:, 6] <= e)
+            else:
+                busy = work > 1.0
+            n = int(busy.sum())
+            row = [n, work[busy].mean() if n else 0.0, work.max(), a.max() - e.max(), r.max() - a.max(), r.max() - b.min()]
+            if gemm:
+                row += [(q[busy, 4] - q[busy, 0]).mean(), (q[busy, 5] - q[busy, 4]).mean(), (q[busy, 6] - q[busy, 5]).mean(), (q[busy, 1] - q[busy, 6]).mean()] if n else [0.0] * 4
+            rows.append(row)
+        m = np.mean(np.array(rows), axis=0)
+        d = {"step": names[s], "busy_workgroups": int(round(m[0])), "work_us_mean": round(m[1], 2), "work_us_slowest": round(m[2], 2),
+             "last_work_to_last_arrival_us": round(m[3], 2), "last_arrival_to_last_release_us": round(m[4], 2), "span_us": round(m[5], 2)}
+        if len(m) > 6:
+            d.update({"wait_for_input_us": round(m[6], 2), "stream_us": round(m[7], 2), "reduce_and_epilogue_us": round(m[8], 2),
+                      "stores_acknowledged_us": round(m[9], 2)})
+        per_layer += m[5]
+        steps.append(d)
+    return {"what": f"one tree_verify_forward of {layers} layers at context {L}, T = {T}: separate launches against the persistent layer kernel; "
+                    "per-step figures are means over the inner layers of in-kernel wall-clock stamps (100 MHz counter)",
+            "ms_separate_launches": round(ms_launches, 4), "ms_layer_kernel": round(ms_kernel, 4),
+            "us_per_layer_in_layer_kernel": round(per_layer, 2), "device_flags": int(flags), "steps": steps}
+
+
 def stage(msg):
     """one progress line per finished stage, on stderr (stdout carries only the JSON line)"""
     print(f"bench.py: {msg}", file=sys.stderr, flush=True)
@@ -234,6 +304,8 @@ def main():
                     help="also time accept_typical (tau 0.7, eps 0.15, alpha sqrt(eps)); the session then keeps the [B,T,V] logits")
     ap.add_argument("--sweep", action="store_true",
                     help="only the tree-size sweep: step time for proposal trees of 1..128 nodes at batch 1..16 and the size of highest expected tokens/s per batch size")
+    ap.add_argument("--layer-kernel-timeline", action="store_true",
+                    help="only the in-kernel timeline of the persistent layer kernel (opt-in path, HYDRA_LAYER_KERNEL=1) against separate launches, on 8 layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--other-configs-budget", type=float, default=75.0,
                     help="seconds the default run may spend on the verify-step figures of configs 3, 4 and 5 (0 = skip them)")
@@ -264,6 +336,11 @@ def main():
         return
     if args.tree:
         cfg = cfg.with_(T=args.tree)
+    if args.layer_kernel_timeline:
+        tl = layer_kernel_timeline(cfg, (args.prompt or cfg.prompt[0]) + 11, "cuda:0")
+        print(json.dumps({"metric": "in-kernel timeline of the persistent layer kernel", "unit": "us", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": f"config {args.config}: {cfg.name} shape, T={cfg.T}, B=1"}, "layer_kernel_timeline": tl}))
+        return
     if args.medusa:
         cfg = cfg.with_(medusa=1)
     tree_name = {16: "tiny16", 32: "prior32", 64: "prior64", 128: "prior128"}[cfg.T]
