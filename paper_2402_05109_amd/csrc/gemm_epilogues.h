@@ -212,7 +212,7 @@ struct EpiQkvRopeT {
     const float *ss; int nb; int Mpad; int dmodel; float eps;
     const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
     a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
-    int kv_touch_max;       // rows with more keys than this are not pre-read (see extra_block)
+    int kv_touch_max;       // no pre-read when the rows of the call hold more keys than this in all (see extra_block)
     static constexpr bool LDS_PROLOGUE = true, PAIRED = true, EXTRA_BLOCKS = true;
     // Workgroups behind the last band group (the q|k|v GEMM of up to 64 rows leaves a quarter of the CUs without
     // one) read this layer's cached K and V pages once, so that tree attention, which follows and is a chain of
@@ -222,6 +222,11 @@ struct EpiQkvRopeT {
     __device__ __forceinline__ void extra_block(int w, int n, const GemmGeom &g) const {
         const int rows = (g.M + T - 1) / T;
         const int n16 = H * Dh * 2;                                  // 16-byte pieces of one page of one layer (16 tokens, all heads)
+        // the limit is on the keys of all rows together: a batch of rows makes attention a throughput problem as a long
+        // row does (at 16 rows of 512 keys the pre-read was 134 MB per layer and took six times as long as the GEMM)
+        int total = 0;
+        for (int b = 0; b < rows; ++b) total += max(seq_len[b], 0) + T;
+        if (total > kv_touch_max) return;                            // uniform over the workgroup
         uint32_t sink = 0u;
         for (int b = 0; b < rows; ++b) {
             const int L = seq_len[b];
