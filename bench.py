@@ -55,13 +55,15 @@ def read_traffic(config):
     name = f"gemm_bf16_kernel_config{config}_traffic.txt"
     path = os.path.join(ROOT, "profiles", name)
     try:
-        val = None
+        val, when = None, None
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
                 val = float(line.split(":")[1])
+            if line.startswith("collected:"):
+                when = line.split(":", 1)[1].strip()
         if val is None:
             return None, None
-        src = f"profiles/{name}"
+        src = f"profiles/{name}" + (f", collected {when}" if when else "")
         try:
             import subprocess
             r = subprocess.run(["git", "-C", ROOT, "log", "-1", "--format=%h %cs", "--", f"profiles/{name}"], capture_output=True, text=True, timeout=10)

@@ -436,6 +436,25 @@ struct RowSource {
 
 // The decoder layers of the context over its B * T tree rows.  lm_tail: final RMSNorm, LM head, argmax (the
 // verify step); otherwise the residual stream after the last layer is left in the workspace's x.
+// LM head, greedy token and margin of the 16-bit family (paper, section 2: the base model's next-token choice at every
+// tree node).  Without a logits buffer the GEMM's epilogue reduces every band to its two best columns and a small
+// kernel merges the bands; with one, the logits go through memory and argmax_kernel reads them back.
+static int lm_head_tail(hydra_ctx *c, hipStream_t s, const void *xg, float *part, int M, RowScale rs, int Mpad, int32_t *argmax,
+                        float *margin, float *logits) {
+    const int d = c->m.d, V = c->m.vocab;
+    const int ld_v = gemm_npad(c, V);
+    const size_t mp = align_up(M, 32);
+    int rc;
+    if (!logits && (size_t)ceil_div(V, 32) * Mpad * 16 <= (size_t)mp * ld_v * 4) {
+        int fused = 0;
+        if ((rc = launch_gemm_top2(c, s, xg, c->arena + c->off_lm_head, M, V, d, part, Mpad, &fused))) return rc;
+        if (fused) return launch_argmax_bands(c, s, part, ceil_div(V, 32), Mpad, rs, M, argmax, margin);
+    }
+    GemmPlan p;
+    if ((rc = launch_gemm(c, s, xg, c->arena + c->off_lm_head, part, M, V, d, &p))) return rc;
+    return launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rs, M, argmax, margin, logits);
+}
+
 static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const RowSource &src, const int32_t *seq_len,
                           const hydra_kv *kv, bool lm_tail, float *hidden, int32_t *argmax, float *margin, float *logits) {
     int rc;
@@ -464,8 +483,7 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
             if ((rc = launch_layers_mega(c, s, B, W + w.mega, seq_len, kv, flags, &io, true))) return rc;
             const RowScale rl = {io.ss_last, io.nb_last, io.Mpad, d, c->m.rms_eps};
             if ((rc = launch_final_hidden(c, s, io.x_last, (const float *)(A + c->off_final_norm), rl, hidden, M))) return rc;
-            if ((rc = launch_gemm(c, s, io.xg_last, A + c->off_lm_head, part, M, V, d, &p))) return rc;
-            return launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rl, M, argmax, margin, logits);
+            return lm_head_tail(c, s, io.xg_last, part, M, rl, io.Mpad, argmax, margin, logits);
         }
         if (src.tokens) { if ((rc = launch_embed_prep(c, s, src.tokens, x, gain0, xa, ss, Mpad, M, flags))) return rc; }
         else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, gain0, xa, ss, Mpad, flags))) return rc; }
@@ -480,9 +498,7 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
         }
         if (!lm_tail) return HYDRA_OK;
         if ((rc = launch_final_hidden(c, s, x, (const float *)(A + c->off_final_norm), rs, hidden, M))) return rc;
-        if ((rc = launch_gemm(c, s, xa, A + c->off_lm_head, part, M, V, d, &p))) return rc;
-        if ((rc = launch_argmax(c, s, part, p.splits, ld_v, mp * ld_v, rs, M, argmax, margin, logits))) return rc;
-        return HYDRA_OK;
+        return lm_head_tail(c, s, xa, part, M, rs, Mpad, argmax, margin, logits);
     }
     if (src.tokens) { if ((rc = launch_embed(c, s, src.tokens, x, M, flags))) return rc; }
     else            { if ((rc = launch_gather_prep(c, s, B, src.hidden, src.T_src, src.path, src.n_acc, x, nullptr, nullptr, nullptr, 0, flags))) return rc; }

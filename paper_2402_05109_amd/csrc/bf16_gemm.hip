@@ -265,6 +265,17 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
     return launch_bf16<EpiResid, NT_ANY>(c, s, X, W, M, N, K, p, epi);
 }
 
+// LM head straight to per-band top-2 candidates (no logits): *fused = 0 and nothing launched where the plan that splits K
+// over workgroups is estimated clearly faster than one workgroup per band group (the candidates need complete sums)
+int launch_gemm_top2(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *cand, int Mpad, int *fused) {
+    const GemmPlan ps = plan_gemm(c, M, N, K, GEMM_KIND_PLAIN);
+    const GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);
+    *fused = (p.shared_x == 0 && p.cost_us <= ps.cost_us + 4.0f && env_or("HYDRA_LM_HEAD_TOP2", 1.0) != 0.0) ? 1 : 0;
+    if (!*fused) return HYDRA_OK;
+    EpiTop2 epi{cand, Mpad, N};
+    return launch_bf16<EpiTop2, NT_ANY>(c, s, X, W, M, N, K, p, epi);
+}
+
 int launch_gemm_silu(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int F, int K, const float *ss,
                      int nb, int Mpad, void *act) {
     GemmPlan p = plan_gemm(c, M, 2 * F, K, GEMM_KIND_SWIGLU);
@@ -317,6 +328,7 @@ int gemm_max_dynamic_lds(hydra_ctx *c) {
     (void)c;
     hipError_t e = set_attr_all<EpiPlain>();
     if (e == hipSuccess) e = set_attr_all<EpiResid>();
+    if (e == hipSuccess) e = set_attr_all<EpiTop2>();
     if (e == hipSuccess) e = set_attr_all<EpiBiasSilu>();
     if (e == hipSuccess) e = set_attr_all<EpiSilu>();
     if (e == hipSuccess) e = set_attr<1, 2, EpiQkvRope>();

@@ -161,6 +161,17 @@ __device__ __forceinline__ void st_dev128(void *p, __attribute__((ext_vector_typ
     }
 }
 
+// running (largest value, its index, second largest value); ties go to the lower index
+struct Top2 { float v1; int i1; float v2; };
+__device__ __forceinline__ void top2_push(Top2 &t, float v, int i) {
+    if (v > t.v1 || (v == t.v1 && i < t.i1)) { t.v2 = t.v1; t.v1 = v; t.i1 = i; }
+    else if (v > t.v2) t.v2 = v;
+}
+__device__ __forceinline__ void top2_merge(Top2 &a, const Top2 &b) {
+    if (b.v1 > a.v1 || (b.v1 == a.v1 && b.i1 < a.i1)) { a.v2 = fmaxf(a.v1, b.v2); a.v1 = b.v1; a.i1 = b.i1; }
+    else a.v2 = fmaxf(a.v2, b.v1);
+}
+
 __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 enum { FLAG_CAPACITY = 1, FLAG_BAD_TOKEN = 2, FLAG_BAD_PATH = 4, FLAG_TIMEOUT = 8, FLAG_SATURATED = 16, FLAG_WEIGHT_UNDERFLOW = 32, FLAG_BAD_PAGE = 64 };

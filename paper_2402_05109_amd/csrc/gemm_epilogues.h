@@ -99,6 +99,37 @@ struct EpiPlainT {
     }
 };
 
+// LM head when only the greedy token and its margin are wanted: instead of the 32x32 tile of logits, each band leaves
+// per row (largest sum, its column, second largest sum) of its 32 columns, cand[band][Mpad] as four floats (the
+// column as integer bits).  Columns at or beyond V (padding of the last band) do not take part.  The sums are left
+// unscaled: argmax_bands_kernel applies the row's 1/rms and merges the bands.
+struct EpiTop2 {
+    float *cand; int Mpad; int V;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
+    template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
+    template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    template <int MB, int NT>
+    __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
+        const int band = t.tile0 + i;
+        if (band >= g.NTiles) return;
+        const int col = band * 32 + (t.lane & 31);
+        f32x4_t *dst = reinterpret_cast<f32x4_t *>(cand) + (size_t)band * Mpad;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = acc_row(t.mb0 + a, v, t.lane);
+            Top2 q = {col < V ? acc[v] : -INFINITY, col < V ? col : 0x7fffffff, -INFINITY};
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) {                                 // over the 32 columns of the band
+                const Top2 u = {__shfl_xor(q.v1, o, 64), __shfl_xor(q.i1, o, 64), __shfl_xor(q.v2, o, 64)};
+                top2_merge(q, u);
+            }
+            if ((t.lane & 31) == 0 && row < g.M) dst[row] = f32x4_t{q.v1, __int_as_float(q.i1), q.v2, 0.f};
+        }
+    }
+};
+
 // Residual branch end: x += acc.  Also leaves what the next RMSNorm'd GEMM needs:
 // xg = half(x * gain) in GEMM input order (the 1/rms factor commutes with the
 // contraction and is applied by the consumer) and ss[band][row] = sum over the

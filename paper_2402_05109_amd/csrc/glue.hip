@@ -278,15 +278,6 @@ int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int p
 // LM head epilogue: per row, logits = sum of split-K partials; greedy token =
 // lowest id among the maxima; margin = top-1 minus top-2 value.
 // ---------------------------------------------------------------------------
-struct Top2 { float v1; int i1; float v2; };
-__device__ __forceinline__ void top2_push(Top2 &t, float v, int i) {
-    if (v > t.v1 || (v == t.v1 && i < t.i1)) { t.v2 = t.v1; t.v1 = v; t.i1 = i; }
-    else if (v > t.v2) t.v2 = v;
-}
-__device__ __forceinline__ void top2_merge(Top2 &a, const Top2 &b) {
-    if (b.v1 > a.v1 || (b.v1 == a.v1 && b.i1 < a.i1)) { a.v2 = fmaxf(a.v1, b.v2); a.v1 = b.v1; a.i1 = b.i1; }
-    else a.v2 = fmaxf(a.v2, b.v1);
-}
 
 // One workgroup of 1024 threads per row.  VEC: rows of `part` are 16-byte aligned (row stride a multiple
 // of 4), so a thread takes four consecutive logits per load and keeps four loads in flight.
@@ -354,6 +345,47 @@ int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int par
     if (vec) hipLaunchKernelGGL(argmax_kernel<true>, dim3(M), dim3(1024), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
     else     hipLaunchKernelGGL(argmax_kernel<false>, dim3(M), dim3(1024), 0, s, part, S, part_ld, split_stride, rs, c->m.vocab, argmax, margin, logits);
     HYDRA_LAUNCH_CHECK("argmax_kernel");
+    return HYDRA_OK;
+}
+
+// The same result from the per-band candidates that the LM-head GEMM's own epilogue leaves when the logits are not
+// asked for (EpiTop2): cand[band][Mpad] = (largest sum of the band, its column, second largest), unscaled.  One
+// workgroup per row merges the bands (value descending, then column ascending) after scaling by the row's 1/rms, which
+// is computed exactly as argmax_kernel computes it, so the margin has the same bits as on that path; the column can
+// differ from it only where two different sums round to the same scaled value (a tie after scaling: that path then
+// reports the lower column of the two, this one the column of the larger unscaled sum; the margin is 0 on both).
+__global__ __launch_bounds__(256) void argmax_bands_kernel(const float4 *__restrict__ cand, int bands, int Mpad, RowScale rs,
+                                                           int32_t *argmax, float *margin) {
+    const int m = blockIdx.x;
+    __shared__ float sh[1];
+    const float r = row_rstd_block(rs, m, sh);
+    Top2 t = {-INFINITY, 0x7fffffff, -INFINITY};
+    for (int b = threadIdx.x; b < bands; b += 256) {
+        const float4 c = cand[(size_t)b * Mpad + m];
+        const Top2 u = {r * c.x, __float_as_int(c.y), r * c.z};
+        top2_merge(t, u);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Top2 u = {__shfl_xor(t.v1, o, 64), __shfl_xor(t.i1, o, 64), __shfl_xor(t.v2, o, 64)};
+        top2_merge(t, u);
+    }
+    __shared__ Top2 red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Top2 q = red[0];
+        for (int w = 1; w < 4; ++w) top2_merge(q, red[w]);
+        argmax[m] = q.i1;
+        if (margin) margin[m] = q.v1 - q.v2;
+    }
+}
+
+int launch_argmax_bands(hydra_ctx *c, hipStream_t s, const float *cand, int bands, int Mpad, RowScale rs, int M, int32_t *argmax,
+                        float *margin) {
+    (void)c;
+    hipLaunchKernelGGL(argmax_bands_kernel, dim3(M), dim3(256), 0, s, reinterpret_cast<const float4 *>(cand), bands, Mpad, rs, argmax, margin);
+    HYDRA_LAUNCH_CHECK("argmax_bands_kernel");
     return HYDRA_OK;
 }
 

@@ -161,6 +161,9 @@ int launch_attention(hydra_ctx *c, hipStream_t s, int B, int layer, const void *
                      const hydra_kv *kv, float *apart, int units, void *x_out, float *plain_out, int32_t *flags);
 int launch_silu_mul(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                     void *x_out, int M);
+int launch_gemm_top2(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *cand, int Mpad, int *fused);
+int launch_argmax_bands(hydra_ctx *c, hipStream_t s, const float *cand, int bands, int Mpad, RowScale rs, int M, int32_t *argmax,
+                        float *margin);
 int launch_argmax(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
                   RowScale rs, int M, int32_t *argmax, float *margin, float *logits);
 int launch_q_import(hydra_ctx *c, hipStream_t s, int B, const float *q_plain, void *qbuf);

@@ -248,6 +248,47 @@ def test_tree_verify_forward_is_bitwise_the_same_without_the_kv_pre_read(monkeyp
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("tree_name,B", [("prior64", 1), ("tiny16", 3), ("prior128", 1), ("single", 2)])
+def test_greedy_token_and_margin_without_a_logits_buffer(tree_name, B, monkeypatch):
+    """Without a logits buffer the LM head's epilogue keeps two candidates per 32-column band and a small kernel merges
+    them; with one, the logits go through memory.  Same inputs through both: hidden states bit-equal, margins
+    bit-equal, tokens equal (a token may differ only where the margin is exactly 0: a tie after scaling).  The
+    vocabulary (1000) ends inside a band.  The switch HYDRA_LM_HEAD_TOP2=0 must give the same bits as well."""
+    cfg = bf16_shape()
+    W = make_weights(cfg, gain_std=0.1, std=0.05)
+    parent = TREES[tree_name]()
+    T = len(parent)
+    lens = [90, 0, 37][:B]
+    rng = np.random.default_rng(21)
+    kvs = [torch.tensor(rng.standard_normal((B, max(lens) + 1, 2, cfg.H, cfg.Dh)) * 0.5, dtype=torch.float32, device="cuda:0") for _ in range(cfg.NL)]
+    toks = torch.stack([uniform_tokens(21, b, T, cfg.V) for b in range(B)]).to(torch.int32)
+    outs = {}
+    for mode, want, env in (("logits", True, "1"), ("top2", False, "1"), ("top2-off", False, "0")):
+        monkeypatch.setenv("HYDRA_LM_HEAD_TOP2", env)
+        sess = gpu_session(cfg, parent, B, 160, W, page_perm_seed=3, want_logits=want)
+        for l in range(cfg.NL):
+            sess.main.kv_write(B, l, sess.kv, 0, max(lens) + 1, kvs[l])
+        sess.seq_len.copy_(torch.tensor(lens, dtype=torch.int32)); sess.host_len = max(lens)
+        o = sess.out()
+        o.tree_tokens.copy_(toks)
+        sess.verify()
+        torch.cuda.synchronize()
+        assert sess.main.read_flags() == 0
+        outs[mode] = (o.hidden.clone(), o.argmax.clone(), o.margin.clone(), o.logits.clone() if want else None)
+    h0, a0, m0, lg = outs["logits"]
+    # the logits path is self-consistent (lowest-index maximum, top-1 minus top-2)
+    top2 = torch.topk(lg, 2, dim=-1).values
+    assert torch.equal(m0, top2[..., 0] - top2[..., 1])
+    for mode in ("top2", "top2-off"):
+        h, a, m, _ = outs[mode]
+        assert torch.equal(h, h0) and torch.equal(m, m0), mode
+        differ = a != a0
+        assert not bool((differ & (m0 != 0)).any()), mode
+        picked = torch.gather(lg, 2, a.long().unsqueeze(-1)).squeeze(-1)
+        assert torch.equal(picked, top2[..., 0]), mode           # whatever was picked carries the maximal logit
+    print(tree_name, B, "tokens that differ at an exact tie:", int((outs["top2"][1] != a0).sum()), flush=True)
+
+
 def _verify_forward_teacher_forced(tree_name, B, L):
     print("case", tree_name, B, L, flush=True)
     cfg = bf16_shape()
