@@ -124,6 +124,13 @@ int launch_gemm_f32(hydra_ctx *c, hipStream_t s, const float *X, const float *W,
 template <int MB, int NT, class Epi>
 static void launch_one(dim3 grid, dim3 block, size_t lds, hipStream_t s, const GemmGeom &g, const Epi &epi, hipEvent_t e0, hipEvent_t e1) {
     constexpr int MAXT = (MB * NT >= 6) ? 256 : 512;
+    if constexpr (MB == 4) {                       // several row groups exist only with four row blocks per workgroup
+        if (g.gz > 1) {
+            if (e0) hipExtLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi, true>), grid, block, lds, s, e0, e1, 0, g, epi);
+            else    hipLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi, true>), grid, block, lds, s, g, epi);
+            return;
+        }
+    }
     if (e0) hipExtLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
     else    hipLaunchKernelGGL((gemm_bf16_kernel<MB, NT, MAXT, Epi>), grid, block, lds, s, g, epi);
 }
@@ -310,6 +317,10 @@ int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void 
 template <int MB, int NT, class Epi>
 static hipError_t set_attr() {
     constexpr int MAXT = (MB * NT >= 6) ? 256 : 512;
+    if constexpr (MB == 4) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<MB, NT, MAXT, Epi, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute((const void *)gemm_bf16_kernel<MB, NT, MAXT, Epi>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 template <class Epi>

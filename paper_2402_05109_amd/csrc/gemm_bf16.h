@@ -100,7 +100,8 @@ struct GemmTile {
 
 // One workgroup of the GEMM: (bx, by, bz) are its band-group, K-split and row-group indices (the plain kernel passes
 // its block indices), red its dynamic LDS.
-template <int MB, int NT, class Epilogue, int GEMM_U>
+// ROWGROUPS: the launch has several row groups (see the load of W and the K walk below)
+template <int MB, int NT, class Epilogue, int GEMM_U, bool ROWGROUPS = false>
 __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue &epi, int bx, int by, int bz, float *red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nw = wave % g.NW, kw = wave / g.NW;
@@ -138,8 +139,8 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
         for (int u = 0; u < GEMM_U; ++u) {
             const int k = min(k0 + u, g.KT - 1);         // clamped: a ragged tail re-reads a valid tile and skips its MFMA
 #pragma unroll
-            for (int i = 0; i < NT; ++i)            // a streaming load where each byte is used once; with four row blocks there may be
-                w[u][i] = MB == 4 ? wrow[i][(size_t)k * 64] : __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // other row groups: keep it in L2
+            for (int i = 0; i < NT; ++i)            // a streaming load where each byte is used once; with several row groups the
+                w[u][i] = ROWGROUPS ? wrow[i][(size_t)k * 64] : __builtin_nontemporal_load(wrow[i] + (size_t)k * 64);   // others on this XCD read the same lines: keep them in L2
 #pragma unroll
             for (int a = 0; a < MB; ++a) x[u][a] = xrow[a][(size_t)k * 64];
         }
@@ -156,13 +157,13 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
             }
         }
     };
-    // Few rows (X is small): k-blocks of U steps are visited in an order rotated by the band-group index, so that
-    // the workgroups streaming different bands do not all ask the L2 for the same X lines at once.  With four row
-    // blocks per workgroup X is large (M x K), and every band group re-reads it: there all workgroups walk K in the
-    // same order, so that the part of X in use at any time fits in L2 (rotated, each band group's X reads missed:
-    // 5-6 times the weight bytes were fetched from memory at 1024 rows).
+    // One row group (X is small): k-blocks of U steps are visited in an order rotated by the band-group index, so
+    // that the workgroups streaming different bands do not all ask the L2 for the same X lines at once.  With several
+    // row groups X is large (M x K), and every band group re-reads it: there all workgroups walk K in the same order,
+    // so that the part of X in use at any time fits in L2 (rotated, each band group's X reads missed: at 1024 rows
+    // the GEMMs fetched 11-13 times their weight bytes from memory).
     const int nblk = ((k_end - s_begin + GEMM_U - 1) / GEMM_U - kw + g.KW - 1) / g.KW;
-    const int rot = (MB < 4 && nblk > 0) ? (int)(((unsigned)bx * 5u) % (unsigned)nblk) : 0;
+    const int rot = (!ROWGROUPS && nblk > 0) ? (int)(((unsigned)bx * 5u) % (unsigned)nblk) : 0;
     auto kof = [&](int j) { int q = j + rot; if (q >= nblk) q -= nblk; return s_begin + (q * g.KW + kw) * GEMM_U; };
     // Two register sets alternate.  The long-run case is its own straight-line region whose refills are
     // unconditional: only then can the compiler count how many loads are younger than the set it is about to
@@ -271,7 +272,7 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
 }
 
 
-template <int MB, int NT, int MAXT, class Epilogue, int GEMM_U = GemmU<MB, NT>::value>
+template <int MB, int NT, int MAXT, class Epilogue, bool ROWGROUPS = false, int GEMM_U = GemmU<MB, NT>::value>
 __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue epi) {
     extern __shared__ float red[];                 // [scratch] + [KW][NW][MB*NT][16][64]
     if constexpr (Epilogue::EXTRA_BLOCKS) {        // workgroups behind the last band group: side work of the epilogue's choosing
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     }
     int bx, by, bz;
     if (!gemm_block(g, bx, by, bz)) return;
-    gemm_bf16_body<MB, NT, Epilogue, GEMM_U>(g, epi, bx, by, bz, red);
+    gemm_bf16_body<MB, NT, Epilogue, GEMM_U, ROWGROUPS>(g, epi, bx, by, bz, red);
 }
 
 // Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
