@@ -89,12 +89,14 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
     // faster at 8): the X tiles both groups read count against the CU's request path even when they hit in L1.
     if (mgroups >= 6 && p.kw >= 2) { p.nw = 2; p.kw >>= 1; }
     p.kpw = ceil_div(KT, p.kw * p.splits);
-    // Two or more row groups of 128 rows: the X tiles dominate, and where enough workgroups remain 4 or 8 waves take
-    // different band pairs and share X through LDS (gemm_bf16_sharedx_kernel; no K split in that shape).  A workgroup
-    // then pulls NWT pairs of W and X once; the shape is taken where that costs less than the plan above.
-    if (p.mb == 4 && mgroups >= 2 && KT >= 16) {
+    // Four row blocks per workgroup: the X tiles dominate what a workgroup pulls, and where enough workgroups remain 4 or 8
+    // waves take different band pairs and share X through LDS (gemm_bf16_sharedx_kernel).  A workgroup then pulls NWT
+    // pairs of W and X once.  Where the output may be split (plain partial outputs), K is also split over workgroups:
+    // that multiplies the workgroups and shortens each one's slice of X (a single row group of 128 rows has only
+    // bands / (2 NWT) workgroups otherwise).  The shape is taken where it costs less than the plan above.
+    if (p.mb == 4 && (mgroups >= 2 || may_split) && KT >= 16) {
         const int groups2 = ceil_div(bands, 2);
-        int pick = 0;
+        int pick = 0, pick_s = 1;
         if (getenv("HYDRA_PLAN_SHARED_X_MIN_WGS")) {                  // tests: the shape wherever this many workgroups remain
             const int min_wgs = (int)env_or("HYDRA_PLAN_SHARED_X_MIN_WGS", 160.0);
             for (int nwt = 8; nwt >= 4 && !pick && mgroups >= 4; nwt >>= 1)
@@ -102,16 +104,25 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
         } else {
             double best = p.cost_us;
             const double hbm = (double)N * K * 2 / (hbm_tbps * 1e6);
-            for (int nwt = 8; nwt >= 4; nwt >>= 1) {
-                const int wgs = ceil_div(groups2, nwt) * mgroups;
-                const double bytes = (double)nwt * 64 * K * 2 + 128.0 * K * 2;
-                double cost = ceil_div(wgs, 256) * bytes / (cap_gbps * 1e3);
-                if (cost < hbm) cost = hbm;
-                if (wgs >= 128 && cost < 0.97 * best) { best = cost; pick = nwt; }      // a tie goes to the plan with more workgroups
-            }
+            const int s_max = (may_split && env_or("HYDRA_PLAN_SHARED_X_SPLIT", 1.0) != 0.0) ? max_split : 1;
+            for (int nwt = 8; nwt >= 4; nwt >>= 1)
+                for (int sp = 1; sp <= s_max; ++sp) {
+                    if (sp > 1 && KT / sp < 16) break;
+                    if (sp == 1 && mgroups < 2) continue;              // one row group, no split: too few workgroups by construction
+                    const int wgs = ceil_div(groups2, nwt) * mgroups * sp;
+                    const double bytes = ((double)nwt * 64 + 128.0) * K * 2 / sp;
+                    double cost = ceil_div(wgs, 256) * bytes / (cap_gbps * 1e3);
+                    if (cost < hbm) cost = hbm;
+                    cost += (sp > 1 ? 1.0 + split_charge * sp : 0.0);
+                    if (wgs >= 128 && cost < 0.97 * best) { best = cost; pick = nwt; pick_s = sp; }      // a tie goes to the plan with more workgroups
+                }
             if (pick) p.cost_us = (float)best;
         }
-        if (pick) { p.shared_x = pick; p.nt = 2; p.nw = pick; p.kw = 1; p.splits = 1; p.kpw = KT; }
+        if (pick) {
+            p.shared_x = pick; p.nt = 2; p.nw = pick; p.kw = 1; p.splits = pick_s;
+            p.kpw = ceil_div(ceil_div(KT, pick_s), 4) * 4;           // k-steps per split: whole blocks of four
+            p.splits = ceil_div(KT, p.kpw);
+        }
     }
     static const bool debug = getenv("HYDRA_PLAN_DEBUG") != nullptr;       // tuning aid: every plan to stderr
     if (debug)
@@ -151,7 +162,7 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
     if (Epi::EXTRA_BLOCKS && !p.shared_x && g.gy == 1 && g.gz == 1) grid.x += extra_blocks;      // see Epilogue::extra_block
     size_t lds = ((size_t)GEMM_LDS_SCRATCH + (p.kw > 1 ? (size_t)p.kw * p.nw * p.mb * p.nt * 16 * 64 : 0)) * 4;
     if (p.shared_x) {
-        if (p.mb != 4 || p.nt != 2 || p.kw != 1 || p.splits != 1 || p.nw != p.shared_x || (p.shared_x != 4 && p.shared_x != 8))
+        if (p.mb != 4 || p.nt != 2 || p.kw != 1 || p.splits < 1 || (p.splits > 1 && !std::is_same<Epi, EpiPlain>::value) || p.nw != p.shared_x || (p.shared_x != 4 && p.shared_x != 8))
             return fail(HYDRA_E_UNSUPPORTED, "gemm: inconsistent shared-X plan");
         lds = ((size_t)GEMM_LDS_SCRATCH + 2 * 4 * 4 * 256) * 4;          // two blocks of 4 k-steps x 4 row blocks of 1 KiB
     }

@@ -306,7 +306,7 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
     t.mb0 = bz * MB;
     t.lane = lane;
     t.wave = wave;
-    t.split = 0;
+    t.split = by;
     t.lds = red;
     constexpr int XT = GEMM_U * MB;                 // X tiles per block
     constexpr int XS = (XT + NWT - 1) / NWT;        // of which this wave fetches up to XS
@@ -324,8 +324,10 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][i][v] = 0.f;
 
-    const int nblk = (g.KT + GEMM_U - 1) / GEMM_U;
-    auto kof = [&](int j) { return j >= nblk ? g.KT - 1 : j * GEMM_U; };      // every workgroup walks K in the same order: the part of X in use fits in L2
+    // grid.y > 1 splits K over workgroups (g.kpw k-steps each; only epilogues that write per-split outputs)
+    const int s_begin = min(g.KT, by * g.kpw), k_end = min(g.KT, s_begin + g.kpw);
+    const int nblk = (k_end - s_begin + GEMM_U - 1) / GEMM_U;
+    auto kof = [&](int j) { return j >= nblk ? k_end : s_begin + j * GEMM_U; };      // every workgroup of a split walks its K range in the same order: the part of X in use fits in L2
     u32x4_t wa[GEMM_U][NT], wb[GEMM_U][NT], xs[XS];
     auto load_w = [&](u32x4_t (&w)[GEMM_U][NT], int k0) {
 #pragma unroll
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(NWT * 64) void gemm_bf16_sharedx_kernel(GemmGeom g,
 #pragma unroll
                 for (int a = 0; a < MB; ++a) xr[(u + 1) & 1][a] = xb[((u + 1) * MB + a) * 64];
             }
-            if (k0 + u < g.KT) {
+            if (k0 + u < k_end) {
 #pragma unroll
                 for (int a = 0; a < MB; ++a)
 #pragma unroll
