@@ -99,6 +99,23 @@ struct EpiPlainT {
     }
 };
 
+// top2_merge without branches (the sixteen rows of a tile are independent chains that the compiler may interleave)
+__device__ __forceinline__ void top2_join(Top2 &a, const Top2 &b) {
+    const bool take = b.v1 > a.v1 || (b.v1 == a.v1 && b.i1 < a.i1);
+    const float loser = take ? a.v1 : b.v1;
+    a.v2 = fmaxf(take ? b.v2 : a.v2, loser);
+    a.v1 = take ? b.v1 : a.v1;
+    a.i1 = take ? b.i1 : a.i1;
+}
+template <int CTRL>
+__device__ __forceinline__ Top2 top2_dpp(const Top2 &q) {
+    Top2 u;
+    u.v1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q.v1), CTRL, 0xf, 0xf, false));
+    u.i1 = __builtin_amdgcn_update_dpp(0, q.i1, CTRL, 0xf, 0xf, false);
+    u.v2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q.v2), CTRL, 0xf, 0xf, false));
+    return u;
+}
+
 // LM head when only the greedy token and its margin are wanted: instead of the 32x32 tile of logits, each band leaves
 // per row (largest sum, its column, second largest sum) of its 32 columns, cand[band][Mpad] as four floats (the
 // column as integer bits).  Columns at or beyond V (padding of the last band) do not take part.  The sums are left
@@ -120,11 +137,13 @@ struct EpiTop2 {
         for (int v = 0; v < 16; ++v) {
             const int row = acc_row(t.mb0 + a, v, t.lane);
             Top2 q = {col < V ? acc[v] : -INFINITY, col < V ? col : 0x7fffffff, -INFINITY};
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) {                                 // over the 32 columns of the band
-                const Top2 u = {__shfl_xor(q.v1, o, 64), __shfl_xor(q.i1, o, 64), __shfl_xor(q.v2, o, 64)};
-                top2_merge(q, u);
-            }
+            // over the 32 columns of the band: four data-parallel-primitive steps inside the rows of 16 lanes (each joins
+            // two disjoint sets of lanes, so no column is counted twice), then one exchange between the two rows
+            top2_join(q, top2_dpp<0xB1>(q));                                   // quad_perm [1,0,3,2]
+            top2_join(q, top2_dpp<0x4E>(q));                                   // quad_perm [2,3,0,1]
+            top2_join(q, top2_dpp<0x141>(q));                                  // row_half_mirror
+            top2_join(q, top2_dpp<0x140>(q));                                  // row_mirror
+            top2_join(q, Top2{__shfl_xor(q.v1, 16, 64), __shfl_xor(q.i1, 16, 64), __shfl_xor(q.v2, 16, 64)});
             if ((t.lane & 31) == 0 && row < g.M) dst[row] = f32x4_t{q.v1, __int_as_float(q.i1), q.v2, 0.f};
         }
     }

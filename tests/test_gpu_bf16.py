@@ -253,7 +253,8 @@ def test_greedy_token_and_margin_without_a_logits_buffer(tree_name, B, monkeypat
     """Without a logits buffer the LM head's epilogue keeps two candidates per 32-column band and a small kernel merges
     them; with one, the logits go through memory.  Same inputs through both: hidden states bit-equal, margins
     bit-equal, tokens equal (a token may differ only where the margin is exactly 0: a tie after scaling).  The
-    vocabulary (1000) ends inside a band.  The switch HYDRA_LM_HEAD_TOP2=0 must give the same bits as well."""
+    vocabulary (1000) ends inside a band.  The band-wise path is opt-in (HYDRA_LM_HEAD_TOP2=1); without the switch a
+    call without a logits buffer must give the same bits too."""
     cfg = bf16_shape()
     W = make_weights(cfg, gain_std=0.1, std=0.05)
     parent = TREES[tree_name]()
