@@ -287,8 +287,8 @@ int launch_gemm_resid(hydra_ctx *c, hipStream_t s, const void *X, const void *W,
 
 // LM head straight to per-band top-2 candidates (no logits): *fused = 0 and nothing launched where the plan that splits K
 // over workgroups is estimated clearly faster than one workgroup per band group (the candidates need complete sums).
-// Opt-in (HYDRA_LM_HEAD_TOP2=1): measured at the 7B shape the per-band reductions in the epilogue cost 11 us where the
-// smaller second kernel saves 6 (58.1 + 5.7 against 47.0 + 11.6 us), so by default the logits go through memory.
+// Opt-in (HYDRA_LM_HEAD_TOP2=1): measured at the 7B shape it is a wash, 50.3 + 5.8 us against 47.0 + 11.6 us at 64 rows and
+// 52.1 + 5.7 against 41.8 + ~8 us for the one-node tree, so by default the logits go through memory.
 int launch_gemm_top2(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, int N, int K, float *cand, int Mpad, int *fused) {
     const GemmPlan ps = plan_gemm(c, M, N, K, GEMM_KIND_PLAIN);
     const GemmPlan p = plan_gemm(c, M, N, K, GEMM_KIND_FUSED);

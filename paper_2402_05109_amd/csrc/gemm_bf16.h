@@ -30,6 +30,8 @@
 //       three may contain a workgroup barrier; what they leave in LDS is visible to tile() because a
 //       barrier separates streaming from the epilogue;
 //   begin(t, g): once per wave after that barrier, before its first tile.
+// An epilogue with ROWWISE = true also has rows(copies, copy_stride, KW, a, i, t, g): where waves split K it is handed the
+// LDS reduction buffer of tile (a, i) instead of the summed registers and reads it in whatever order suits it.
 // An epilogue with PAIRED = true (NT = 2 or 4: one or two band pairs per wave) instead receives both tiles of a
 // band pair, four accumulator registers (rows) at a time:  pair4(x0, x1, a, v0, t, g) with x0[q], x1[q] the
 // registers v0 + q of the pair's tiles in row block a, and t.tile0 the pair's first band.  The 4*MB items of
@@ -237,7 +239,10 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmGeom &g, const Epilogue
     __syncthreads();
     if (!live) return;
     epi.begin(t, g);
-    if constexpr (Epilogue::PAIRED) {
+    if constexpr (Epilogue::ROWWISE) {                             // the epilogue reads the tile row by row out of the reduction buffer itself
+        for (int j = kw; j < TILES; j += g.KW)                     // wave-uniform
+            epi.rows(redbuf + ((size_t)nw * TILES + j) * 16 * 64, (size_t)g.NW * TILES * 16 * 64, g.KW, j / NT, j % NT, t, g);
+    } else if constexpr (Epilogue::PAIRED) {
         for (int id = kw; id < MB * 4 * (NT / 2); id += g.KW) {    // wave-uniform
             const int pr = id / (MB * 4), r = id - pr * (MB * 4);
             const int a = r >> 2, v0 = (r & 3) * 4;

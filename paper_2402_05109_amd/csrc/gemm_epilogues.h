@@ -82,7 +82,7 @@ __device__ __forceinline__ void rstd_table(float *lds, int lane, int wave, int d
 template <bool DEV>
 struct EpiPlainT {
     float *out; int ld; size_t split_stride;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false, ROWWISE = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
@@ -122,11 +122,41 @@ __device__ __forceinline__ Top2 top2_dpp(const Top2 &q) {
 // unscaled: argmax_bands_kernel applies the row's 1/rms and merges the bands.
 struct EpiTop2 {
     float *cand; int Mpad; int V;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false, ROWWISE = true;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
     template <int MB, int NT> __device__ __forceinline__ void begin(const GemmTile<MB, NT> &, const GemmGeom &) const {}
+    // The same from the workgroup's LDS reduction buffer (waves that split K): copies[w * copy_stride + v * 64 + lane] is
+    // accumulator register v of K-split wave w.  Here a lane takes one ROW of the tile and half of its 32 columns, adds
+    // the copies in wave order and keeps a running top-2, so one exchange between the two halves finishes the row (the
+    // column-wise way above needs a reduction across lanes for each of the 16 registers).  Row r of the tile lives in
+    // register 4 * (r / 8) + r % 4 of the lanes 32 * ((r % 8) / 4) + column; the columns are visited in an order rotated
+    // by the row, so that the 32 lanes of a half read 32 different LDS banks.
+    template <int MB, int NT>
+    __device__ __forceinline__ void rows(const float *copies, size_t copy_stride, int KW, int a, int i, const GemmTile<MB, NT> &t,
+                                         const GemmGeom &g) const {
+        const int band = t.tile0 + i;
+        if (band >= g.NTiles) return;
+        const int r = t.lane & 31, h = t.lane >> 5;
+        const float *src = copies + (4 * (r >> 3) + (r & 3)) * 64 + 32 * ((r & 7) >> 2);
+        float x[16];
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) x[jj] = 0.f;
+        for (int w = 0; w < KW; ++w) {                                         // sixteen independent reads per copy, added in wave order
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) x[jj] += src[(size_t)w * copy_stride + ((jj + r + 16 * h) & 31)];
+        }
+        Top2 q = {-INFINITY, 0x7fffffff, -INFINITY};
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int col = band * 32 + ((jj + r + 16 * h) & 31);
+            top2_join(q, Top2{col < V ? x[jj] : -INFINITY, col < V ? col : 0x7fffffff, -INFINITY});
+        }
+        top2_join(q, Top2{__shfl_xor(q.v1, 32, 64), __shfl_xor(q.i1, 32, 64), __shfl_xor(q.v2, 32, 64)});
+        const int row = 32 * (t.mb0 + a) + r;
+        if (h == 0 && row < g.M) reinterpret_cast<f32x4_t *>(cand)[(size_t)band * Mpad + row] = f32x4_t{q.v1, __int_as_float(q.i1), q.v2, 0.f};
+    }
     template <int MB, int NT>
     __device__ __forceinline__ void tile(const f32x16_t &acc, int a, int i, const GemmTile<MB, NT> &t, const GemmGeom &g) const {
         const int band = t.tile0 + i;
@@ -155,7 +185,7 @@ struct EpiTop2 {
 // band's 32 columns of x^2.
 struct EpiResid {
     float *x; int d; const float *gain; a16_t *xg; float *ss; int Mpad; int32_t *flags;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false, ROWWISE = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
@@ -200,7 +230,7 @@ struct EpiResid {
 template <bool DEV>
 struct EpiSiluT {
     const float *ss; int nb; int Mpad; int dmodel; float eps; a16_t *act; int F; int32_t *flags;
-    static constexpr bool LDS_PROLOGUE = true, PAIRED = false, EXTRA_BLOCKS = false;
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = false, EXTRA_BLOCKS = false, ROWWISE = false;
     template <int MB, int NT> __device__ __forceinline__ RowSumRegs issue(const GemmTile<MB, NT> &t, const GemmGeom &) const {
         return rowsum_issue<MB>(ss, nb, Mpad, t.mb0 * 32, t.lane, t.wave, 0);
     }
@@ -263,7 +293,7 @@ struct EpiQkvRopeT {
     const int32_t *seq_len; const TreeDev *tree; const int32_t *page_table; int max_pages, n_pages, layer;
     a16_t *kpages, *vpages, *qbuf; const float *rope; int H, Dh, T, max_pos; int32_t *flags;
     int kv_touch_max;       // no pre-read when the rows of the call hold more keys than this in all (see extra_block)
-    static constexpr bool LDS_PROLOGUE = true, PAIRED = true, EXTRA_BLOCKS = true;
+    static constexpr bool LDS_PROLOGUE = true, PAIRED = true, EXTRA_BLOCKS = true, ROWWISE = false;
     // Workgroups behind the last band group (the q|k|v GEMM of up to 64 rows leaves a quarter of the CUs without
     // one) read this layer's cached K and V pages once, so that tree attention, which follows and is a chain of
     // dependent round trips, finds them in the memory-side cache.  Nothing is computed from the values.  Only for
@@ -415,7 +445,7 @@ struct EpiQkvRopeT {
 // Draft-head MLP layer: z = (residual ? z : 0) + SiLU(acc + bias), fp32 and as next GEMM input
 struct EpiBiasSilu {
     const float *bias; float *z; int d; int residual; a16_t *xg; int32_t *flags;
-    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false;
+    static constexpr bool LDS_PROLOGUE = false, PAIRED = false, EXTRA_BLOCKS = false, ROWWISE = false;
     template <int MB, int NT> __device__ __forceinline__ NoPre issue(const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ NoPre prologue(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const { return NoPre{}; }
     template <int MB, int NT> __device__ __forceinline__ void before_barrier(NoPre, const GemmTile<MB, NT> &, const GemmGeom &) const {}
