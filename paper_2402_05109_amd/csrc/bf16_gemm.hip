@@ -173,12 +173,16 @@ static int launch_bf16(hydra_ctx *c, hipStream_t s, const void *X, const void *W
         e0 = c->ev[c->ev_used++]; e1 = c->ev[c->ev_used++];
     }
     const int key = p.mb * 10 + p.nt;
-    if (p.shared_x == 8) {
-        if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
-        else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, g, epi);
-    } else if (p.shared_x == 4) {
-        if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
-        else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, g, epi);
+    if (p.shared_x) {
+        if constexpr (std::is_same<Epi, EpiTop2>::value) {           // never planned for this epilogue (launch_gemm_top2): no such kernel is built
+            return fail(HYDRA_E_UNSUPPORTED, "gemm: the band-wise top-2 epilogue has no shared-X kernel");
+        } else if (p.shared_x == 8) {
+            if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
+            else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 8, Epi>), grid, block, lds, s, g, epi);
+        } else {
+            if (e0) hipExtLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, e0, e1, 0, g, epi);
+            else    hipLaunchKernelGGL((gemm_bf16_sharedx_kernel<4, 2, 4, Epi>), grid, block, lds, s, g, epi);
+        }
     } else if constexpr (NT_SET == NT_TWO) {
         switch (key) {
             case 12: launch_one<1, 2>(grid, block, lds, s, g, epi, e0, e1); break;
