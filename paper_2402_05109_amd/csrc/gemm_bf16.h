@@ -289,11 +289,12 @@ __global__ __launch_bounds__(MAXT) void gemm_bf16_kernel(GemmGeom g, Epilogue ep
     gemm_bf16_body<MB, NT, Epilogue, GEMM_U, ROWGROUPS>(g, epi, bx, by, bz, red);
 }
 
-// Variant for many rows (four row blocks per workgroup, several row groups): the X tiles dominate what a workgroup
-// pulls through its CU's request path, so here the NWT waves of a workgroup take different band groups, all walk
-// the whole of K block by block in step, and share the X tiles of a block through LDS: each wave fetches 1/NWT of
-// them, two blocks live in LDS, one workgroup barrier per block.  W still goes straight to registers, two sets
-// alternating.  No wave splits K, so the epilogue runs on the wave's own accumulators.
+// Variant for many rows (four row blocks per workgroup): the X tiles dominate what a workgroup pulls through its CU's
+// request path, so here the NWT waves of a workgroup take different band groups, all walk the workgroup's K range
+// block by block in step, and share the X tiles of a block through LDS: each wave fetches 1/NWT of them, two blocks
+// live in LDS, one workgroup barrier per block.  W still goes straight to registers, two sets alternating.  No wave
+// splits K, so the epilogue runs on the wave's own accumulators; grid.y may split K over workgroups (g.kpw k-steps
+// each) for epilogues that write per-split outputs.
 //   iteration j: multiply block j (X from LDS buffer j % 2) | refill the W set just used with block j + 2 |
 //   barrier (every wave is done with buffer j % 2) | store the fetched X share of block j + 2 there |
 //   request the share of block j + 3.
