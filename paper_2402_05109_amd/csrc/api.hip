@@ -490,7 +490,7 @@ static int forward_layers(hydra_ctx *c, hipStream_t s, int B, void *ws, const Ro
         for (int l = 0; l < c->m.n_layers; ++l) {
             const LayerOff &o = c->layer[l];
             const float *next_gain = (const float *)(A + (l + 1 < c->m.n_layers ? c->layer[l + 1].attn_norm : c->off_final_norm));
-            if ((rc = launch_gemm_qkv_rope(c, s, xa, A + o.wqkv, M, rs, l, seq_len, kv, qbuf, flags))) return rc;
+            if ((rc = launch_gemm_qkv_rope(c, s, xa, A + o.wqkv, M, rs, l, seq_len, kv, qbuf, part, flags))) return rc;
             if ((rc = launch_attention(c, s, B, l, qbuf, seq_len, kv, apart, w.attn_units, xb, nullptr, flags))) return rc;
             if ((rc = launch_gemm_resid(c, s, xb, A + o.wo, M, d, d, x, (const float *)(A + o.ffn_norm), xa, ss, Mpad, part, &rs.nb))) return rc;
             if ((rc = launch_gemm_silu(c, s, xa, A + o.wgu, M, F, d, ss, rs.nb, Mpad, xb))) return rc;

@@ -318,7 +318,27 @@ int launch_gemm_bias_silu(hydra_ctx *c, hipStream_t s, const void *X, const void
 
 // q|k|v projection, rotary embedding and cache append in one kernel (bf16 family)
 int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, RowScale rs, int layer,
-                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags) {
+                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, float *part, int32_t *flags) {
+    {
+        // Beyond 128 rows a plan that splits K over workgroups (plain partial sums, then rotary embedding and cache append
+        // as a kernel of their own) can beat the fused one: each workgroup pulls a shorter slice of X (measured: steps at
+        // 192 rows 7.7 -> 7.3 ms, the 33B shape at 256 rows 30.8 -> 29.5 ms; at 96 and 128 rows it lost 1.5 %).  It is taken where
+        // the planner's estimate plus the cost of the second kernel is lower (HYDRA_PLAN_QKV_UNFUSED: 0 never, 1 always).
+        const int dd = c->m.d;
+        const GemmPlan pf = plan_gemm(c, M, 3 * dd, dd, GEMM_KIND_PAIRS), pu = plan_gemm(c, M, 3 * dd, dd, GEMM_KIND_PLAIN);
+        const int mode = (int)env_or("HYDRA_PLAN_QKV_UNFUSED", -1.0);
+        // the second kernel: its launch, and S partial outputs of M x 3d floats read back at about 4 TB/s
+        const float second = 5.0f + (float)((double)pu.splits * M * 3 * dd * 4 / 4e6);
+        const bool unfused = mode == 1 || (mode != 0 && M > 128 && pu.splits > 1 && pu.cost_us + second < pf.cost_us);
+        if (unfused) {
+            const int npad = gemm_npad(c, 3 * dd);
+            const size_t stride = (size_t)ceil_div(M, 32) * 32 * npad;
+            EpiPlain epi{part, npad, stride};
+            int rc = launch_bf16<EpiPlain, NT_ANY>(c, s, X, W, M, 3 * dd, dd, pu, epi);
+            if (rc) return rc;
+            return launch_rope_append(c, s, part, pu.splits, npad, stride, rs, M / c->tree.T, layer, seq_len, kv, qbuf, flags);
+        }
+    }
     const int d = c->m.d;
     GemmPlan p = plan_gemm(c, M, 3 * d, d, GEMM_KIND_PAIRS);
     EpiQkvRope epi{rs.ss, rs.nb, rs.Mpad, d, rs.eps, seq_len, tree_dev(c), kv->page_table, kv->max_pages, kv->n_pages, layer,

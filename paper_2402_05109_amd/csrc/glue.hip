@@ -176,6 +176,13 @@ __device__ __forceinline__ size_t q_index(int b, int n, int h, int dim, int H, i
     }
 }
 
+// 16-bit family: rounded to half with the saturation flag, as the fused epilogue of the q|k|v GEMM does
+template <bool BF>
+__device__ __forceinline__ void qkv_store(typename Act<BF>::type *p, size_t i, float v, int32_t *flags) {
+    if constexpr (BF) p[i] = f2a_f(v, flags);
+    else p[i] = v;
+}
+
 template <bool BF>
 __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t split_stride, RowScale rs, const TreeDev *tree,
                                    const float *rope, const int32_t *seq_len, const int32_t *page_table,
@@ -199,21 +206,24 @@ __global__ void rope_append_kernel(const float *part, int S, int part_ld, size_t
     const int j = threadIdx.x;
     if (j >= half) return;
     const size_t row = (size_t)m * part_ld;
-    const int c0 = h * Dh + j, c1 = c0 + half;
-    const float q0 = r * part_sum(part, S, split_stride, row + c0), q1 = r * part_sum(part, S, split_stride, row + c1);
-    const float k0 = r * part_sum(part, S, split_stride, row + d + c0), k1 = r * part_sum(part, S, split_stride, row + d + c1);
+    const int c0 = h * Dh + j, c1 = c0 + half;                  // v columns (and q, k in the fp32 family): the natural order
+    // 16-bit family: the q and k weight bands of a head are packed so that the bands holding dims j and j + Dh/2 are
+    // neighbours (pack_weight_kernel, bph > 1): dim j < Dh/2 sits in band 2 * (j / 32), dim j + Dh/2 in the band behind it
+    const int p0 = BF ? h * Dh + 2 * (j >> 5) * 32 + (j & 31) : c0, p1 = BF ? p0 + 32 : c1;
+    const float q0 = r * part_sum(part, S, split_stride, row + p0), q1 = r * part_sum(part, S, split_stride, row + p1);
+    const float k0 = r * part_sum(part, S, split_stride, row + d + p0), k1 = r * part_sum(part, S, split_stride, row + d + p1);
     const float v0 = r * part_sum(part, S, split_stride, row + 2 * d + c0), v1 = r * part_sum(part, S, split_stride, row + 2 * d + c1);
     const float cs = rope[((size_t)pos * half + j) * 2], sn = rope[((size_t)pos * half + j) * 2 + 1];
-    Act<BF>::st(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn);
-    Act<BF>::st(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn);
+    qkv_store<BF>(qbuf, q_index<BF>(b, n, h, j, H, Dh, T), q0 * cs - q1 * sn, flags);
+    qkv_store<BF>(qbuf, q_index<BF>(b, n, h, j + half, H, Dh, T), q1 * cs + q0 * sn, flags);
     const int page = page_table[(size_t)b * max_pages + (slot >> 4)];
     if ((unsigned)page >= (unsigned)n_pages) { atomicOr(flags, FLAG_BAD_PAGE); return; }      // bad table entry: the row's K/V are not written
     const int tok = slot & 15;
     const size_t base = kv_block_base(layer, n_pages, page, H, h, Dh);
-    Act<BF>::st(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn);
-    Act<BF>::st(kpages, base + k_in_block<BF>(tok, j + half, Dh), k1 * cs + k0 * sn);
-    Act<BF>::st(vpages, base + v_in_block<BF>(tok, j, Dh), v0);
-    Act<BF>::st(vpages, base + v_in_block<BF>(tok, j + half, Dh), v1);
+    qkv_store<BF>(kpages, base + k_in_block<BF>(tok, j, Dh), k0 * cs - k1 * sn, flags);
+    qkv_store<BF>(kpages, base + k_in_block<BF>(tok, j + half, Dh), k1 * cs + k0 * sn, flags);
+    qkv_store<BF>(vpages, base + v_in_block<BF>(tok, j, Dh), v0, flags);
+    qkv_store<BF>(vpages, base + v_in_block<BF>(tok, j + half, Dh), v1, flags);
 }
 
 int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, int part_ld, size_t split_stride,
@@ -221,8 +231,12 @@ int launch_rope_append(hydra_ctx *c, hipStream_t s, const float *part, int S, in
                        int32_t *flags) {
     const int T = c->tree.T;
     dim3 grid(B * T, c->m.n_heads), block(64);
-    // the bf16 family does this step in the epilogue of its q|k|v GEMM (launch_gemm_qkv_rope)
-    if (c->bf16) return fail(HYDRA_E_UNSUPPORTED, "rope_append: fp32 family only");
+    // the bf16 family does this step in the epilogue of its q|k|v GEMM unless the plan splits K (launch_gemm_qkv_rope)
+    if (c->bf16) {
+        hipLaunchKernelGGL(rope_append_kernel<true>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (a16_t *)kv->k_pages, (a16_t *)kv->v_pages, (a16_t *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
+        HYDRA_LAUNCH_CHECK("rope_append_kernel");
+        return HYDRA_OK;
+    }
     hipLaunchKernelGGL(rope_append_kernel<false>, grid, block, 0, s, part, S, part_ld, split_stride, rs, tree_dev(c), rope_dev(c), seq_len, kv->page_table, kv->max_pages, kv->n_pages, layer, (float *)kv->k_pages, (float *)kv->v_pages, (float *)qbuf, c->m.d, c->m.n_heads, c->m.head_dim, c->m.max_pos, flags);
     HYDRA_LAUNCH_CHECK("rope_append_kernel");
     return HYDRA_OK;

@@ -124,7 +124,7 @@ int attn_max_dynamic_lds(hydra_ctx *c);
 // per-row 1/rms from the per-band sums of squares ss[band][Mpad] (bf16 family); ss == NULL: no scaling
 struct RowScale { const float *ss; int nb; int Mpad; int d; float eps; };
 int launch_gemm_qkv_rope(hydra_ctx *c, hipStream_t s, const void *X, const void *W, int M, RowScale rs, int layer,
-                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, int32_t *flags);
+                         const int32_t *seq_len, const hydra_kv *kv, void *qbuf, float *part, int32_t *flags);
 int launch_embed_prep(hydra_ctx *c, hipStream_t s, const int32_t *tokens, float *x, const float *gain, void *xg,
                       float *ss, int Mpad, int M, int32_t *flags);
 int launch_final_hidden(hydra_ctx *c, hipStream_t s, const float *x, const float *gain, RowScale rs, float *hidden, int M);

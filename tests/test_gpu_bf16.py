@@ -220,6 +220,14 @@ def test_tree_verify_forward_five_bands_per_wave_in_gate_up(tree_name, B, L, mon
     _verify_forward_teacher_forced(tree_name, B, L)
 
 
+@pytest.mark.parametrize("tree_name,B,L", [("prior64", 2, 33), ("prior128", 1, 200), ("tiny16", 3, 0), ("prior64", 1, 95)])
+def test_tree_verify_forward_with_rotary_and_append_as_their_own_kernel(tree_name, B, L, monkeypatch):
+    """Beyond 128 rows the planner may split K of the q|k|v GEMM over workgroups and leave rotary embedding and cache
+    append to a second kernel (which has to undo the pairing of the packed q and k bands); forced here for every shape."""
+    monkeypatch.setenv("HYDRA_PLAN_QKV_UNFUSED", "1")
+    _verify_forward_teacher_forced(tree_name, B, L)
+
+
 def test_tree_verify_forward_is_bitwise_the_same_without_the_kv_pre_read(monkeypatch):
     """The spare workgroups of the q|k|v launch only read cached K/V pages ahead of attention; switching them off
     must not change a single bit of any output (rows of different lengths, one of them empty)."""
