@@ -101,6 +101,8 @@ GemmPlan plan_gemm(const hydra_ctx *c, int M, int N, int K, int kind) {
             const int min_wgs = (int)env_or("HYDRA_PLAN_SHARED_X_MIN_WGS", 160.0);
             for (int nwt = 8; nwt >= 4 && !pick && mgroups >= 4; nwt >>= 1)
                 if (ceil_div(groups2, nwt) * mgroups >= min_wgs) pick = nwt;
+            const int sp = (int)env_or("HYDRA_PLAN_SHARED_X_SPLITS", 1.0);       // tests: with this many K splits where the output may be split
+            if (pick && may_split && sp > 1 && KT / sp >= 4) pick_s = sp;
         } else {
             double best = p.cost_us;
             const double hbm = (double)N * K * 2 / (hbm_tbps * 1e6);

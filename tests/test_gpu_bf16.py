@@ -204,6 +204,15 @@ def test_tree_verify_forward_many_rows_kernel_on_a_small_model(min_wgs, monkeypa
     _verify_forward_teacher_forced("prior64", 16, 21)
 
 
+@pytest.mark.parametrize("splits", [2, 3])
+def test_tree_verify_forward_many_rows_kernel_with_k_split_over_workgroups(splits, monkeypatch):
+    """The same kernel with K also split over workgroups wherever the output is a plain partial sum (O, down, LM head):
+    two and three splits, the latter with a ragged last split in the down projection (24 k-steps in blocks of four)."""
+    monkeypatch.setenv("HYDRA_PLAN_SHARED_X_MIN_WGS", "1")
+    monkeypatch.setenv("HYDRA_PLAN_SHARED_X_SPLITS", str(splits))
+    _verify_forward_teacher_forced("prior64", 16, 21)
+
+
 @pytest.mark.parametrize("tree_name,B,L", [("prior64", 1, 21), ("tiny16", 3, 17), ("single", 2, 9), ("prior32", 1, 40)])
 def test_tree_verify_forward_two_band_pairs_per_wave(tree_name, B, L, monkeypatch):
     """The q|k|v GEMM with two band pairs per wave (the planner takes that shape when one pair per wave would need a
